@@ -1,0 +1,135 @@
+/*
+ * moe_gfx950 -- C ABI of the single-GPU hot path of a Mixture-of-Experts layer on MI355X (gfx950).
+ *
+ * One forward of the layer (paper Section 2.1, Fig. 2): every token row of the receive buffer is
+ * dispatched to its topk experts, goes through the two feed-forward GEMMs of each expert
+ * (layer0: [H x F], activation, layer1: [F x H]) and the topk results are reduced back into one
+ * row per token.  The two producer/consumer pipelines of Section 3 (dispatch -> GroupGEMM, and
+ * GroupGEMM -> top-k reduce) meet in shared tensors of M*topk rows (Fig. 4); this library runs
+ * both on one GPU, with the receive buffer split into per-source segments that stand for the
+ * peers of Section 3.1.2.
+ *
+ * Conventions
+ *   - Every pointer marked "dev" is device memory on the current HIP device, owned by the caller,
+ *     16-byte aligned, row-major and contiguous.  "host" pointers are ordinary host memory.
+ *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE fp32).
+ *   - The library owns only the plan object.  moe_layer_forward and the other enqueueing calls
+ *     allocate nothing, never synchronise the host and only enqueue work on the given stream.
+ *   - Every call returns a moe_status_t (0 = OK, negative = error).  Nothing throws or aborts.
+ *   - Symbols: T tokens (paper's M), H embedding size (paper's N), F expert hidden size (paper's
+ *     K), E experts, k = topk, R = T*k rows of the shared tensors, S source segments.
+ */
+#ifndef MOE_GFX950_H
+#define MOE_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_plan moe_plan_t; /* opaque, host side, owned by the library */
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = -1,        /* NULL pointer, misaligned pointer, bad enum / key / value */
+  MOE_ERR_SHAPE_MISMATCH = -2,     /* call arguments disagree with the plan (e.g. act) */
+  MOE_ERR_WORKSPACE_TOO_SMALL = -3,
+  MOE_ERR_UNSUPPORTED = -4,        /* shape outside what the kernels handle (see moe_plan_create) */
+  MOE_ERR_HIP = -5,                /* a HIP runtime call failed; hipGetLastError has the detail */
+  MOE_ERR_TIMEOUT = -6             /* a bounded wait on a ready flag expired (debug spin bound only) */
+} moe_status_t;
+
+typedef enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 } moe_act_t;
+
+typedef struct {
+  int32_t T; /* tokens in the receive buffer */
+  int32_t H; /* embedding size */
+  int32_t F; /* expert hidden size */
+  int32_t E; /* experts held by this GPU */
+  int32_t k; /* experts per token */
+  int32_t S; /* source segments of the receive buffer */
+  int32_t act; /* moe_act_t */
+} moe_shape_t;
+
+/* Plan / variant selection (Section 3.2.2: the division point between data-movement and GEMM
+ * workgroups and the kernel variant are chosen per shape before launch and looked up at run time).
+ * seg_offsets: host, [S+1], non-decreasing, seg_offsets[0] = 0, seg_offsets[S] = T; segment s is the
+ * token range [seg_offsets[s], seg_offsets[s+1]) written by source s.  Copied into the plan.
+ * Supported: H % 256 == 0, F % 128 == 0 (F % 256 == 0 for GELU), 1 <= k <= E <= 256, k <= 16,
+ * 1 <= S <= 64, T*k < 2^24.  Touches no GPU state.  *plan is set only on success. */
+int moe_plan_create(moe_plan_t **plan, const moe_shape_t *shape, const int32_t *seg_offsets);
+int moe_plan_destroy(moe_plan_t *plan);
+
+/* Tunables.  Keys:
+ *   "tile_m"       64 / 128 / 256: rows of a GroupGEMM tile (default: chosen from T*k/E)
+ *   "n_dm"         data-movement workgroups of the layer1 kernel (default: table lookup per shape)
+ *   "layer1_order" 0 = expert-major tiles, separate combine kernel afterwards;
+ *                  1 = column-panel-major tiles (Fig. 6), combine workgroups inside the GEMM kernel
+ *   "layer0_order" 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5)
+ *   "spin_limit"   >0: a wait on a ready flag gives up after that many polls and the forward
+ *                  reports MOE_ERR_TIMEOUT through moe_last_device_status (0 = wait for ever)
+ *   "phases"       bit mask of the steps a forward runs: 1 index build, 2 layer0, 4 layer1, 8 combine
+ *                  (default 15; used to time the phases alone)
+ * Unknown key or out-of-range value: MOE_ERR_INVALID_ARG. */
+int moe_plan_set_option(moe_plan_t *plan, const char *key, int64_t value);
+int moe_plan_get_option(const moe_plan_t *plan, const char *key, int64_t *value);
+
+/* Bytes of device workspace a forward needs: index arrays, tile tables, flags and counters, the
+ * activation buffer h [R,F] bf16 and the layer1 shared tensor Y [R,H] bf16 (Fig. 4). */
+size_t moe_plan_workspace_bytes(const moe_plan_t *plan);
+
+/* Size in bytes of the receive (communication) buffer for M tokens of N bf16 elements: 2*M*N
+ * (Section 5.5, Table 3).  This is the x argument of moe_layer_forward. */
+size_t moe_receive_buffer_bytes(int64_t M, int64_t N);
+
+/* Gate (Section 2.1): softmax over the E logits of each token, keep the k largest, renormalise
+ * the kept probabilities to sum 1.  Slot 0 is the most probable expert; equal logits go to the
+ * lower expert id.  logits: dev fp32 [T,E]; topk_ids: dev int32 [T,k]; topk_weights: dev fp32 [T,k]. */
+int moe_route_topk(const float *logits, int32_t T, int32_t E, int32_t k, int32_t *topk_ids, float *topk_weights,
+                   void *hip_stream);
+
+/* One forward of the layer on one GPU's share (Sections 3.1-3.2):
+ *   index build   row order of the shared tensor: grouped by expert, inside an expert in source
+ *                 order (Section 3.1.2, Fig. 5); tile tables and tile schedules
+ *   layer0        GroupGEMM over gathered rows of x, row indices held in registers (Section 4),
+ *                 activation fused, h [R,F] bf16; a tile starts once the source segment of its
+ *                 last row is ready
+ *   layer1        GroupGEMM h x W2 -> Y [R,H], column-panel-major (Fig. 6), with the top-k
+ *                 weighted reduction done by data-movement workgroups of the same kernel as soon
+ *                 as a column panel is complete (Section 3.2.1, Fig. 7)
+ * x: dev bf16 [T,H] receive buffer.  topk_ids: dev int32 [T,k], values in [0,E) (not checked).
+ * topk_weights: dev fp32 [T,k].  W1: dev bf16 [E,H,F] (GELU) or [E,H,2F] (SwiGLU: columns [0,F)
+ * gate, [F,2F) up).  W2: dev bf16 [E,F,H].  out: dev bf16 [T,H], out[t] = sum_j w[t,j] * FFN_e(t,j)(x[t]).
+ * workspace: dev, >= moe_plan_workspace_bytes, 256-byte aligned; its index arrays stay readable until the
+ * next forward on it.  seg_ready: dev uint32 [S] or NULL; segment s counts as arrived once
+ * seg_ready[s] >= ready_epoch (written by whoever fills the segment, after the data); NULL = all
+ * segments are ready.  act must equal the plan's.  Inputs are not modified. */
+int moe_layer_forward(moe_plan_t *plan, const void *x, const int32_t *topk_ids, const float *topk_weights,
+                      const void *W1, const void *W2, int32_t act, void *out, void *workspace,
+                      size_t workspace_bytes, const uint32_t *seg_ready, uint32_t ready_epoch, void *hip_stream);
+
+/* Copies the index outputs of the last forward on this workspace into caller memory (dev pointers;
+ * enqueued on the stream; any of the four may be NULL):
+ * expert_counts [E], expert_offsets [E+1], perm [R] (sorted row -> pair id t*k+j), inv_perm [R]. */
+int moe_get_index_outputs(const moe_plan_t *plan, const void *workspace, int32_t *expert_counts,
+                          int32_t *expert_offsets, int32_t *perm, int32_t *inv_perm, void *hip_stream);
+
+/* Tile table of the layer0 GroupGEMM as built by the last forward (dev pointers, each [max_tiles],
+ * entries beyond *n_tiles untouched; n_tiles: dev int32 [1]): expert, first sorted row, rows, and
+ * the source segment the tile waits for.  max_tiles >= moe_plan_max_tiles(plan). */
+int moe_get_tile_table(const moe_plan_t *plan, const void *workspace, int32_t *n_tiles, int32_t *tile_expert,
+                       int32_t *tile_row0, int32_t *tile_rows, int32_t *tile_ready_seg, void *hip_stream);
+int32_t moe_plan_max_tiles(const moe_plan_t *plan);
+
+/* Status word written by the kernels of the last forward (0, or MOE_ERR_TIMEOUT when a bounded
+ * flag wait expired).  Synchronises the stream. */
+int moe_last_device_status(const moe_plan_t *plan, const void *workspace, void *hip_stream);
+
+const char *moe_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_GFX950_H */

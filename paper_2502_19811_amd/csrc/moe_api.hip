@@ -1,0 +1,381 @@
+// Host side of libmoe_gfx950: plan object, workspace layout, and the extern "C" entry points.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "moe_internal.h"
+
+using namespace moe;
+
+struct moe_plan {
+  Shape s;
+  int32_t seg_offsets[kMaxSegments + 1];
+  // options
+  int32_t tile_m;
+  int32_t n_dm;          // -1: table lookup
+  int32_t layer0_order;
+  int32_t layer1_order;
+  int32_t spin_limit;
+  int32_t phases;
+  int32_t n_cu;          // 0: not queried yet
+  // derived
+  int32_t n_index_blocks;
+  int32_t max_tiles;
+  int32_t n_tiles_n0, n_tiles_n1;
+  size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
+      off_tile_row0, off_tile_rows, off_tile_ready, off_items0, off_items1, off_panel_done, off_h, off_Y, total_bytes;
+};
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+void layout(moe_plan* p) {
+  const Shape& s = p->s;
+  p->n_index_blocks = (s.R + kIndexChunk - 1) / kIndexChunk;
+  if (p->n_index_blocks < 1) p->n_index_blocks = 1;
+  p->max_tiles = s.R / p->tile_m + s.E;
+  p->n_tiles_n0 = s.act == MOE_ACT_SWIGLU ? s.F / (kTileN / 2) : s.F / kTileN;
+  p->n_tiles_n1 = s.H / kTileN;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes, 256);
+    return at;
+  };
+  p->off_status = take(16 * 4);
+  p->off_counts = take((size_t)s.E * 4);
+  p->off_offsets = take((size_t)(s.E + 1) * 4);
+  p->off_perm = take((size_t)s.R * 4);
+  p->off_inv_perm = take((size_t)s.R * 4);
+  p->off_row_token = take((size_t)s.R * 4);
+  p->off_block_hist = take((size_t)p->n_index_blocks * s.E * 4);
+  p->off_tile_expert = take((size_t)p->max_tiles * 4);
+  p->off_tile_row0 = take((size_t)p->max_tiles * 4);
+  p->off_tile_rows = take((size_t)p->max_tiles * 4);
+  p->off_tile_ready = take((size_t)p->max_tiles * 4);
+  p->off_items0 = take((size_t)p->max_tiles * p->n_tiles_n0 * 4);
+  p->off_items1 = take((size_t)p->max_tiles * p->n_tiles_n1 * 4);
+  p->off_panel_done = take((size_t)p->n_tiles_n1 * 4);
+  p->off_h = take((size_t)s.R * s.F * 2);
+  p->off_Y = take((size_t)s.R * s.H * 2);
+  p->total_bytes = o;
+}
+
+Workspace view(const moe_plan* p, void* base) {
+  char* b = (char*)base;
+  Workspace w;
+  w.status = (int32_t*)(b + p->off_status);
+  w.counts = (int32_t*)(b + p->off_counts);
+  w.offsets = (int32_t*)(b + p->off_offsets);
+  w.perm = (int32_t*)(b + p->off_perm);
+  w.inv_perm = (int32_t*)(b + p->off_inv_perm);
+  w.row_token = (int32_t*)(b + p->off_row_token);
+  w.block_hist = (int32_t*)(b + p->off_block_hist);
+  w.tile_expert = (int32_t*)(b + p->off_tile_expert);
+  w.tile_row0 = (int32_t*)(b + p->off_tile_row0);
+  w.tile_rows = (int32_t*)(b + p->off_tile_rows);
+  w.tile_ready = (int32_t*)(b + p->off_tile_ready);
+  w.items0 = (uint32_t*)(b + p->off_items0);
+  w.items1 = (uint32_t*)(b + p->off_items1);
+  w.panel_done = (uint32_t*)(b + p->off_panel_done);
+  w.h = (uint16_t*)(b + p->off_h);
+  w.Y = (uint16_t*)(b + p->off_Y);
+  return w;
+}
+
+int default_tile_m(const Shape& s) {
+  const int mean_rows = s.E > 0 ? s.R / s.E : 0;
+  if (mean_rows >= 1024) return 256;
+  if (mean_rows >= 192) return 128;
+  return 64;
+}
+
+// Division point between GEMM and data-movement workgroups of the layer1 kernel (Section 3.2.2): looked up
+// from the shape.  The entries come from sweeps on MI355X; shapes in between take the nearest rule.
+int default_n_dm(const Shape& s) {
+  const double combine_bytes = 2.0 * s.R * s.H + 2.0 * s.T * s.H;         // Y read + out written
+  const double gemm_flop = 2.0 * s.R * (double)s.F * s.H;
+  // bytes of data movement per flop of GEMM, scaled so that the Mixtral-shaped layer gets 8 of 256
+  double ratio = combine_bytes / gemm_flop * 2.5e15 / 4.0e12 * 0.03;
+  int n = (int)(ratio * 256 + 0.5);
+  if (n < 2) n = 2;
+  if (n > 64) n = 64;
+  return n;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* seg_offsets) {
+  if (!plan || !shape || !seg_offsets) return MOE_ERR_INVALID_ARG;
+  const moe_shape_t& sh = *shape;
+  if (sh.T < 0 || sh.H <= 0 || sh.F <= 0 || sh.E <= 0 || sh.k <= 0 || sh.S <= 0) return MOE_ERR_INVALID_ARG;
+  if (sh.act != MOE_ACT_GELU && sh.act != MOE_ACT_SWIGLU) return MOE_ERR_INVALID_ARG;
+  if (sh.k > sh.E) return MOE_ERR_INVALID_ARG;
+  if (sh.E > kMaxExperts || sh.k > kMaxTopK || sh.S > kMaxSegments) return MOE_ERR_UNSUPPORTED;
+  if (sh.H % 256 != 0) return MOE_ERR_UNSUPPORTED;
+  if (sh.F % (sh.act == MOE_ACT_SWIGLU ? 128 : 256) != 0) return MOE_ERR_UNSUPPORTED;
+  if ((int64_t)sh.T * sh.k >= (1 << 24)) return MOE_ERR_UNSUPPORTED;
+  // row offsets inside the kernels are 32-bit byte offsets
+  if ((int64_t)sh.T * sh.H * 2 >= (1ll << 32) || (int64_t)sh.T * sh.k * sh.F * 2 >= (1ll << 32)) return MOE_ERR_UNSUPPORTED;
+  if (seg_offsets[0] != 0 || seg_offsets[sh.S] != sh.T) return MOE_ERR_INVALID_ARG;
+  for (int i = 0; i < sh.S; i++)
+    if (seg_offsets[i + 1] < seg_offsets[i]) return MOE_ERR_INVALID_ARG;
+  moe_plan* p = new (std::nothrow) moe_plan();
+  if (!p) return MOE_ERR_INVALID_ARG;
+  memset(p, 0, sizeof(*p));
+  p->s.T = sh.T; p->s.H = sh.H; p->s.F = sh.F; p->s.E = sh.E; p->s.k = sh.k; p->s.S = sh.S; p->s.act = sh.act;
+  p->s.R = sh.T * sh.k;
+  p->s.F1 = sh.act == MOE_ACT_SWIGLU ? 2 * sh.F : sh.F;
+  memcpy(p->seg_offsets, seg_offsets, sizeof(int32_t) * (sh.S + 1));
+  p->tile_m = default_tile_m(p->s);
+  p->n_dm = -1;
+  p->layer0_order = 0;
+  p->layer1_order = 1;
+  p->spin_limit = 0;
+  p->phases = 15;
+  p->n_cu = 0;
+  layout(p);
+  *plan = p;
+  return MOE_OK;
+}
+
+int moe_plan_destroy(moe_plan_t* plan) {
+  delete plan;
+  return MOE_OK;
+}
+
+int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
+  if (!p || !key) return MOE_ERR_INVALID_ARG;
+  if (!strcmp(key, "tile_m")) {
+    if (v != 64 && v != 128 && v != 256) return MOE_ERR_INVALID_ARG;
+    p->tile_m = (int32_t)v;
+    layout(p);
+    return MOE_OK;
+  }
+  if (!strcmp(key, "n_dm")) {
+    if (v < -1 || v > 240) return MOE_ERR_INVALID_ARG;
+    p->n_dm = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "layer0_order")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->layer0_order = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "layer1_order")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->layer1_order = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "spin_limit")) {
+    if (v < 0 || v > 0x7fffffff) return MOE_ERR_INVALID_ARG;
+    p->spin_limit = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "phases")) {
+    if (v < 0 || v > 15) return MOE_ERR_INVALID_ARG;
+    p->phases = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "n_cu")) {
+    if (v < 8 || v > 1024) return MOE_ERR_INVALID_ARG;
+    p->n_cu = (int32_t)v;
+    return MOE_OK;
+  }
+  return MOE_ERR_INVALID_ARG;
+}
+
+int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
+  if (!p || !key || !v) return MOE_ERR_INVALID_ARG;
+  if (!strcmp(key, "tile_m")) *v = p->tile_m;
+  else if (!strcmp(key, "n_dm")) *v = p->n_dm >= 0 ? p->n_dm : default_n_dm(p->s);
+  else if (!strcmp(key, "layer0_order")) *v = p->layer0_order;
+  else if (!strcmp(key, "layer1_order")) *v = p->layer1_order;
+  else if (!strcmp(key, "spin_limit")) *v = p->spin_limit;
+  else if (!strcmp(key, "phases")) *v = p->phases;
+  else if (!strcmp(key, "n_cu")) *v = p->n_cu;
+  else return MOE_ERR_INVALID_ARG;
+  return MOE_OK;
+}
+
+size_t moe_plan_workspace_bytes(const moe_plan_t* p) { return p ? p->total_bytes : 0; }
+
+int32_t moe_plan_max_tiles(const moe_plan_t* p) { return p ? p->max_tiles : 0; }
+
+size_t moe_receive_buffer_bytes(int64_t M, int64_t N) { return (M < 0 || N < 0) ? 0 : (size_t)(2 * M * N); }
+
+int moe_route_topk(const float* logits, int32_t T, int32_t E, int32_t k, int32_t* topk_ids, float* topk_weights,
+                   void* hip_stream) {
+  if (!logits || !topk_ids || !topk_weights) return MOE_ERR_INVALID_ARG;
+  if (T < 0 || E <= 0 || k <= 0 || k > E) return MOE_ERR_INVALID_ARG;
+  if (E > kMaxExperts || k > 64) return MOE_ERR_UNSUPPORTED;
+  return launch_route_topk(logits, T, E, k, topk_ids, topk_weights, (hipStream_t)hip_stream) == hipSuccess ? MOE_OK
+                                                                                                            : MOE_ERR_HIP;
+}
+
+int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, const float* topk_weights, const void* W1,
+                      const void* W2, int32_t act, void* out, void* workspace, size_t workspace_bytes,
+                      const uint32_t* seg_ready, uint32_t ready_epoch, void* hip_stream) {
+  if (!p || !x || !topk_ids || !topk_weights || !W1 || !W2 || !out || !workspace) return MOE_ERR_INVALID_ARG;
+  if (act != p->s.act) return MOE_ERR_SHAPE_MISMATCH;
+  if (workspace_bytes < p->total_bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+  if (!aligned16(x) || !aligned16(W1) || !aligned16(W2) || !aligned16(out) || !aligned16(topk_ids) ||
+      !aligned16(topk_weights) || ((uintptr_t)workspace & 255))
+    return MOE_ERR_INVALID_ARG;
+  const Shape& s = p->s;
+  if (s.T == 0) return MOE_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (p->n_cu == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return MOE_ERR_HIP;
+    p->n_cu = n;
+  }
+  Workspace ws = view(p, workspace);
+
+  if (p->phases & 1) {
+    IndexParams ip;
+    memset(&ip, 0, sizeof(ip));
+    ip.s = s;
+    ip.ws = ws;
+    ip.topk_ids = topk_ids;
+    ip.n_blocks = p->n_index_blocks;
+    ip.tile_m = p->tile_m;
+    ip.n_tiles_n0 = p->n_tiles_n0;
+    ip.n_tiles_n1 = p->n_tiles_n1;
+    ip.layer0_order = p->layer0_order;
+    ip.layer1_order = p->layer1_order;
+    memcpy(ip.seg_offsets, p->seg_offsets, sizeof(int32_t) * (s.S + 1));
+    if (launch_index_build(ip, st) != hipSuccess) return MOE_ERR_HIP;
+  }
+
+  GemmParams g;
+  memset(&g, 0, sizeof(g));
+  g.tile_expert = ws.tile_expert;
+  g.tile_row0 = ws.tile_row0;
+  g.tile_rows = ws.tile_rows;
+  g.tile_ready = ws.tile_ready;
+  g.status = ws.status;
+  g.spin_limit = (uint32_t)p->spin_limit;
+  g.n_tiles = ws.status + 1;
+  g.F = s.F;
+  g.T = s.T;
+  g.k = s.k;
+  g.H = s.H;
+
+  if (p->phases & 2) {
+    GemmParams a = g;
+    a.A = (const char*)x;
+    a.lda_bytes = (uint32_t)s.H * 2;
+    a.a_rows = ws.row_token;
+    a.B = (const char*)W1;
+    a.b_expert_bytes = (uint64_t)s.H * s.F1 * 2;
+    a.ldb = (uint32_t)s.F1;
+    a.C = ws.h;
+    a.ldc = (uint32_t)s.F;
+    a.K = s.H;
+    a.items = ws.items0;
+    a.n_items = ws.status + 2;
+    a.seg_ready = seg_ready;
+    a.ready_epoch = ready_epoch;
+    a.n_mfma = p->n_cu;
+    if (launch_layer0(a, p->tile_m, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
+  }
+
+  const bool fused = p->layer1_order == 1 && (p->phases & 8);
+  if (p->phases & 4) {
+    GemmParams b = g;
+    b.A = (const char*)ws.h;
+    b.lda_bytes = (uint32_t)s.F * 2;
+    b.a_rows = nullptr;
+    b.B = (const char*)W2;
+    b.b_expert_bytes = (uint64_t)s.F * s.H * 2;
+    b.ldb = (uint32_t)s.H;
+    b.C = ws.Y;
+    b.ldc = (uint32_t)s.H;
+    b.K = s.F;
+    b.items = ws.items1;
+    b.n_items = ws.status + 3;
+    b.panel_done = ws.panel_done;
+    int n_dm = fused ? (p->n_dm >= 0 ? p->n_dm : default_n_dm(s)) : 0;
+    if (n_dm > p->n_cu - 8) n_dm = p->n_cu - 8;
+    b.n_mfma = p->n_cu - n_dm;
+    b.fused_combine = fused ? 1 : 0;
+    b.inv_perm = ws.inv_perm;
+    b.topk_weights = topk_weights;
+    b.out = (uint16_t*)out;
+    b.combine_counter = ws.status + 4;
+    if (launch_layer1(b, p->tile_m, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
+  }
+  if ((p->phases & 8) && !(fused && (p->phases & 4))) {
+    CombineParams c;
+    c.Y = ws.Y;
+    c.inv_perm = ws.inv_perm;
+    c.topk_weights = topk_weights;
+    c.out = (uint16_t*)out;
+    c.T = s.T;
+    c.k = s.k;
+    c.H = s.H;
+    if (launch_combine(c, st) != hipSuccess) return MOE_ERR_HIP;
+  }
+  return MOE_OK;
+}
+
+int moe_get_index_outputs(const moe_plan_t* p, const void* workspace, int32_t* expert_counts, int32_t* expert_offsets,
+                          int32_t* perm, int32_t* inv_perm, void* hip_stream) {
+  if (!p || !workspace) return MOE_ERR_INVALID_ARG;
+  Workspace ws = view(p, const_cast<void*>(workspace));
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Shape& s = p->s;
+  auto cp = [&](void* dst, const void* src, size_t bytes) {
+    return !dst || bytes == 0 || hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) == hipSuccess;
+  };
+  if (!cp(expert_counts, ws.counts, (size_t)s.E * 4) || !cp(expert_offsets, ws.offsets, (size_t)(s.E + 1) * 4) ||
+      !cp(perm, ws.perm, (size_t)s.R * 4) || !cp(inv_perm, ws.inv_perm, (size_t)s.R * 4))
+    return MOE_ERR_HIP;
+  return MOE_OK;
+}
+
+int moe_get_tile_table(const moe_plan_t* p, const void* workspace, int32_t* n_tiles, int32_t* tile_expert,
+                       int32_t* tile_row0, int32_t* tile_rows, int32_t* tile_ready_seg, void* hip_stream) {
+  if (!p || !workspace) return MOE_ERR_INVALID_ARG;
+  Workspace ws = view(p, const_cast<void*>(workspace));
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t tb = (size_t)p->max_tiles * 4;
+  auto cp = [&](void* dst, const void* src, size_t bytes) {
+    return !dst || bytes == 0 || hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) == hipSuccess;
+  };
+  if (!cp(n_tiles, ws.status + 1, 4) || !cp(tile_expert, ws.tile_expert, tb) || !cp(tile_row0, ws.tile_row0, tb) ||
+      !cp(tile_rows, ws.tile_rows, tb) || !cp(tile_ready_seg, ws.tile_ready, tb))
+    return MOE_ERR_HIP;
+  return MOE_OK;
+}
+
+int moe_last_device_status(const moe_plan_t* p, const void* workspace, void* hip_stream) {
+  if (!p || !workspace) return MOE_ERR_INVALID_ARG;
+  Workspace ws = view(p, const_cast<void*>(workspace));
+  int32_t v = 0;
+  if (hipMemcpyAsync(&v, ws.status, 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream) != hipSuccess) return MOE_ERR_HIP;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return MOE_ERR_HIP;
+  return v;
+}
+
+const char* moe_status_string(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_INVALID_ARG: return "invalid argument";
+    case MOE_ERR_SHAPE_MISMATCH: return "arguments disagree with the plan";
+    case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MOE_ERR_UNSUPPORTED: return "shape not supported";
+    case MOE_ERR_HIP: return "HIP runtime error";
+    case MOE_ERR_TIMEOUT: return "wait on a ready flag timed out";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

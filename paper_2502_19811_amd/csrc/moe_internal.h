@@ -1,0 +1,108 @@
+// Internal declarations shared by the kernels and the host API of libmoe_gfx950.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe_gfx950.h"
+
+namespace moe {
+
+constexpr int kMaxExperts = 256;
+constexpr int kMaxTopK = 16;
+constexpr int kMaxSegments = 64;
+constexpr int kIndexChunk = 1024;   // (token, slot) pairs handled by one workgroup of the index build
+constexpr int kTileN = 256;         // columns of B staged per GroupGEMM tile
+constexpr int kTileK = 32;          // depth of one LDS stage
+constexpr int kStages = 4;          // LDS stages in flight
+constexpr int kCombineChunk = 32;   // tokens per unit of combine work
+
+// Item of a GroupGEMM schedule: M-tile index in the high 20 bits, N-tile index in the low 12.
+__host__ __device__ inline uint32_t pack_item(uint32_t m_tile, uint32_t n_tile) { return (m_tile << 12) | n_tile; }
+
+// Device-side view of the workspace (all pointers into the caller's workspace buffer).
+struct Workspace {
+  int32_t* status;        // [16]  0: device status word, 1: n_tiles, 2: n_items layer0, 3: n_items layer1,
+                          //       4: combine unit counter, 5: layer0 queue counter, 6: layer1 queue counter
+  int32_t* counts;        // [E]
+  int32_t* offsets;       // [E+1]
+  int32_t* perm;          // [R] sorted row -> pair id
+  int32_t* inv_perm;      // [R] pair id -> sorted row
+  int32_t* row_token;     // [R] sorted row -> token (row of x to gather)
+  int32_t* block_hist;    // [n_index_blocks * E] per-block counts, then per-block bases
+  int32_t* tile_expert;   // [max_tiles]
+  int32_t* tile_row0;     // [max_tiles]
+  int32_t* tile_rows;     // [max_tiles]
+  int32_t* tile_ready;    // [max_tiles] source segment the tile waits for
+  uint32_t* items0;       // [max_tiles * n_tiles_n0] layer0 schedule
+  uint32_t* items1;       // [max_tiles * n_tiles_n1] layer1 schedule
+  uint32_t* panel_done;   // [n_tiles_n1] finished M-tiles per column panel of layer1
+  uint16_t* h;            // [R,F] bf16 activation buffer
+  uint16_t* Y;            // [R,H] bf16 layer1 shared tensor
+};
+
+struct Shape {
+  int32_t T, H, F, E, k, S, act;
+  int32_t R, F1;
+};
+
+struct IndexParams {
+  Shape s;
+  Workspace ws;
+  const int32_t* topk_ids;
+  int32_t n_blocks;
+  int32_t tile_m;
+  int32_t n_tiles_n0, n_tiles_n1;
+  int32_t layer0_order, layer1_order;
+  int32_t seg_offsets[kMaxSegments + 1];
+};
+
+struct GemmParams {
+  const char* A;            // x (layer0) or h (layer1), bf16
+  uint32_t lda_bytes;
+  const int32_t* a_rows;    // layer0: sorted row -> row of A (gather); layer1: nullptr (identity)
+  const char* B;            // W1 or W2
+  uint64_t b_expert_bytes;  // bytes between experts
+  uint32_t ldb;             // elements per row of B
+  uint16_t* C;              // h (layer0) or Y (layer1)
+  uint32_t ldc;             // elements per row of C
+  int32_t K;                // reduction length
+  int32_t F;                // expert hidden size (gate/up split of W1 columns)
+  const int32_t* tile_expert;
+  const int32_t* tile_row0;
+  const int32_t* tile_rows;
+  const int32_t* tile_ready;
+  const uint32_t* items;
+  const int32_t* n_items;   // device scalar
+  const uint32_t* seg_ready;
+  uint32_t ready_epoch;
+  uint32_t spin_limit;
+  int32_t* status;
+  // layer1 only
+  uint32_t* panel_done;
+  const int32_t* n_tiles;   // device scalar: M-tiles in total
+  int32_t n_mfma;           // workgroups doing GEMM tiles; the rest are data-movement workgroups
+  int32_t fused_combine;    // 1: data-movement workgroups reduce finished panels inside this kernel
+  // combine
+  const int32_t* inv_perm;
+  const float* topk_weights;
+  uint16_t* out;
+  int32_t T, k, H;
+  int32_t* combine_counter;
+};
+
+struct CombineParams {
+  const uint16_t* Y;
+  const int32_t* inv_perm;
+  const float* topk_weights;
+  uint16_t* out;
+  int32_t T, k, H;
+};
+
+// kernel launchers (defined in the .hip files)
+hipError_t launch_route_topk(const float* logits, int T, int E, int k, int32_t* ids, float* w, hipStream_t st);
+hipError_t launch_index_build(const IndexParams& p, hipStream_t st);
+hipError_t launch_layer0(const GemmParams& p, int tile_m, int act, int grid, hipStream_t st);
+hipError_t launch_layer1(const GemmParams& p, int tile_m, int grid, hipStream_t st);
+hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+
+}  // namespace moe
