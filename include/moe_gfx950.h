@@ -72,6 +72,9 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  reports MOE_ERR_TIMEOUT through moe_last_device_status (0 = wait for ever)
  *   "phases"       bit mask of the steps a forward runs: 1 index build, 2 layer0, 4 layer1, 8 combine
  *                  (default 15; used to time the phases alone)
+ *   "n_cu"         workgroups of the persistent kernels (default: compute units of the device)
+ *   "profile"      1: every forward records HIP events on its stream before and after each phase
+ *                  (this call then creates the events; read them with moe_plan_phase_times)
  * Unknown key or out-of-range value: MOE_ERR_INVALID_ARG. */
 int moe_plan_set_option(moe_plan_t *plan, const char *key, int64_t value);
 int moe_plan_get_option(const moe_plan_t *plan, const char *key, int64_t *value);
@@ -122,6 +125,11 @@ int moe_get_index_outputs(const moe_plan_t *plan, const void *workspace, int32_t
 int moe_get_tile_table(const moe_plan_t *plan, const void *workspace, int32_t *n_tiles, int32_t *tile_expert,
                        int32_t *tile_row0, int32_t *tile_rows, int32_t *tile_ready_seg, void *hip_stream);
 int32_t moe_plan_max_tiles(const moe_plan_t *plan);
+
+/* Average time in ms of the four phases (index build, layer0 kernel, layer1 kernel incl. fused combine,
+ * stand-alone combine) over the forwards recorded since the last call (at most 64), from the events of the
+ * "profile" option.  ms: host [4]; n_steps: host [1].  Waits for the recorded forwards to finish. */
+int moe_plan_phase_times(moe_plan_t *plan, float *ms, int32_t *n_steps);
 
 /* Status word written by the kernels of the last forward (0, or MOE_ERR_TIMEOUT when a bounded
  * flag wait expired).  Synchronises the stream. */

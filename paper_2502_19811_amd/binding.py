@@ -19,7 +19,7 @@ EXPORTS = [
     "moe_plan_create", "moe_plan_destroy", "moe_plan_set_option", "moe_plan_get_option",
     "moe_plan_workspace_bytes", "moe_plan_max_tiles", "moe_receive_buffer_bytes", "moe_route_topk",
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
-    "moe_status_string",
+    "moe_status_string", "moe_plan_phase_times",
 ]
 
 
@@ -74,6 +74,8 @@ def load_library():
     lib.moe_get_tile_table.restype = C.c_int
     lib.moe_last_device_status.argtypes = [C.c_void_p, vp, vp]
     lib.moe_last_device_status.restype = C.c_int
+    lib.moe_plan_phase_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+    lib.moe_plan_phase_times.restype = C.c_int
     lib.moe_status_string.argtypes = [C.c_int]
     lib.moe_status_string.restype = C.c_char_p
     _lib = lib
@@ -164,3 +166,11 @@ def moe_get_tile_table(plan: int, workspace, n_tiles, tile_expert, tile_row0, ti
 
 def moe_last_device_status(plan: int, workspace, stream=None) -> int:
     return load_library().moe_last_device_status(plan, _ptr(workspace), _stream(stream))
+
+
+def moe_plan_phase_times(plan: int):
+    """(ms per phase [index build, layer0, layer1 (+fused combine), stand-alone combine], forwards averaged)."""
+    ms = (C.c_float * 4)()
+    n = C.c_int32()
+    _check(load_library().moe_plan_phase_times(plan, ms, C.byref(n)), "moe_plan_phase_times")
+    return [float(v) for v in ms], n.value

@@ -7,6 +7,8 @@
 
 using namespace moe;
 
+constexpr int kProfSlots = 64;
+
 struct moe_plan {
   Shape s;
   int32_t seg_offsets[kMaxSegments + 1];
@@ -18,6 +20,10 @@ struct moe_plan {
   int32_t spin_limit;
   int32_t phases;
   int32_t n_cu;          // 0: not queried yet
+  int32_t profile;       // 1: record events around the phases of every forward
+  int32_t prof_steps;    // forwards recorded since the last reset
+  hipEvent_t ev[kProfSlots][5];
+  bool ev_created;
   // derived
   int32_t n_index_blocks;
   int32_t max_tiles;
@@ -145,6 +151,9 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
 }
 
 int moe_plan_destroy(moe_plan_t* plan) {
+  if (plan && plan->ev_created)
+    for (int i = 0; i < kProfSlots; i++)
+      for (int j = 0; j < 5; j++) (void)hipEventDestroy(plan->ev[i][j]);
   delete plan;
   return MOE_OK;
 }
@@ -187,6 +196,18 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     p->n_cu = (int32_t)v;
     return MOE_OK;
   }
+  if (!strcmp(key, "profile")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    if (v == 1 && !p->ev_created) {
+      for (int i = 0; i < kProfSlots; i++)
+        for (int j = 0; j < 5; j++)
+          if (hipEventCreate(&p->ev[i][j]) != hipSuccess) return MOE_ERR_HIP;
+      p->ev_created = true;
+    }
+    p->profile = (int32_t)v;
+    p->prof_steps = 0;
+    return MOE_OK;
+  }
   return MOE_ERR_INVALID_ARG;
 }
 
@@ -199,6 +220,7 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   else if (!strcmp(key, "spin_limit")) *v = p->spin_limit;
   else if (!strcmp(key, "phases")) *v = p->phases;
   else if (!strcmp(key, "n_cu")) *v = p->n_cu;
+  else if (!strcmp(key, "profile")) *v = p->profile;
   else return MOE_ERR_INVALID_ARG;
   return MOE_OK;
 }
@@ -237,6 +259,9 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     p->n_cu = n;
   }
   Workspace ws = view(p, workspace);
+  hipEvent_t* ev = p->profile ? p->ev[p->prof_steps % kProfSlots] : nullptr;
+  auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
+  if (!mark(0)) return MOE_ERR_HIP;
 
   if (p->phases & 1) {
     IndexParams ip;
@@ -253,6 +278,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     memcpy(ip.seg_offsets, p->seg_offsets, sizeof(int32_t) * (s.S + 1));
     if (launch_index_build(ip, st) != hipSuccess) return MOE_ERR_HIP;
   }
+
+  if (!mark(1)) return MOE_ERR_HIP;
 
   GemmParams g;
   memset(&g, 0, sizeof(g));
@@ -287,6 +314,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     if (launch_layer0(a, p->tile_m, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
 
+  if (!mark(2)) return MOE_ERR_HIP;
+
   const bool fused = p->layer1_order == 1 && (p->phases & 8);
   if (p->phases & 4) {
     GemmParams b = g;
@@ -312,6 +341,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.combine_counter = ws.status + 4;
     if (launch_layer1(b, p->tile_m, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
+  if (!mark(3)) return MOE_ERR_HIP;
   if ((p->phases & 8) && !(fused && (p->phases & 4))) {
     CombineParams c;
     c.Y = ws.Y;
@@ -323,6 +353,27 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     c.H = s.H;
     if (launch_combine(c, st) != hipSuccess) return MOE_ERR_HIP;
   }
+  if (!mark(4)) return MOE_ERR_HIP;
+  if (ev) p->prof_steps++;
+  return MOE_OK;
+}
+
+int moe_plan_phase_times(moe_plan_t* p, float* ms, int32_t* n_steps) {
+  if (!p || !ms || !n_steps) return MOE_ERR_INVALID_ARG;
+  const int n = p->prof_steps < kProfSlots ? p->prof_steps : kProfSlots;
+  *n_steps = n;
+  for (int j = 0; j < 4; j++) ms[j] = 0.f;
+  if (n == 0) return MOE_OK;
+  for (int i = 0; i < n; i++) {
+    if (hipEventSynchronize(p->ev[i][4]) != hipSuccess) return MOE_ERR_HIP;
+    for (int j = 0; j < 4; j++) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, p->ev[i][j], p->ev[i][j + 1]) != hipSuccess) return MOE_ERR_HIP;
+      ms[j] += t;
+    }
+  }
+  for (int j = 0; j < 4; j++) ms[j] /= n;
+  p->prof_steps = 0;
   return MOE_OK;
 }
 
