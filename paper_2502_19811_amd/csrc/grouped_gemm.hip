@@ -50,19 +50,6 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Scheduling hint: alternate one MFMA with one LDS read so the reads hide in the MFMA shadow.
-template <int N_READS, int N_MFMA>
-__device__ __forceinline__ void interleave_hint() {
-  constexpr int P = N_READS < N_MFMA ? N_READS : N_MFMA;
-#pragma unroll
-  for (int q = 0; q < P; q++) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-  }
-  if constexpr (N_MFMA > P) __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA - P, 0);
-  if constexpr (N_READS > P) __builtin_amdgcn_sched_group_barrier(0x100, N_READS - P, 0);
-}
-
 // GELU in its erf form, 0.5 v (1 + erf(v / sqrt 2)).  erf is evaluated with the classic 5-term rational
 // approximation 1 - (a1 t + ... + a5 t^5) exp(-z^2), t = 1 / (1 + 0.3275911 z) (absolute error below 1.5e-7,
 // far under the bf16 rounding of the result); it needs a handful of registers, which matters next to 256
@@ -166,7 +153,6 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   constexpr int LA = BM / 64;  // A loads per lane per stage
   constexpr int LB = 4;        // B loads per lane per stage
   constexpr int LS = LA + LB;
-  constexpr int N_READS = MT + 2 * NT;
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int32_t lds_slot;
@@ -254,45 +240,61 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
 #pragma unroll
       for (int j = 0; j < NT; j++) acc[i][j] = (f32x16){0};
 
-    auto issue = [&](int stage) {
-      const uint32_t sa = lds0 + stage * STAGE;
-#pragma unroll
-      for (int j = 0; j < LA; j++) dma16(Ab, aoff[j], sa + (w * LA + j) * 1024);
-#pragma unroll
-      for (int j = 0; j < LB; j++) dma16(Bb, boff[j], sa + A_STAGE + (w * LB + j) * 1024);
+    // One stage = LA loads of A rows and LB loads of B rows per lane.  The loads are issued one at a time between
+    // groups of MFMAs: a burst would fill the vector-memory queue and stall the MFMAs queued behind it.
+    auto issue_a = [&](int stage, int j) { dma16(Ab, aoff[j], lds0 + stage * STAGE + (w * LA + j) * 1024); };
+    auto issue_b = [&](int stage, int j) { dma16(Bb, boff[j], lds0 + stage * STAGE + A_STAGE + (w * LB + j) * 1024); };
+    auto advance = [&]() {
       Ab += BK * 2;
       Bb += bstep;
     };
     bf16x8 af[2][MT], bfr[2][NT];
-    auto mfma_all = [&](int buf) {
+    // Group q (of 4) of a half step: the LDS reads of fragment q for the next half step and a quarter of the MFMAs
+    // of this one.  rd_off / rd_kk: stage offset and 16-deep sub-step the fragments are read from.
+    auto group = [&](int cur, int nxt, uint32_t rd_off, int rd_kk, int q) {
+      constexpr int PER = MT * NT / 4;
+      if (q < MT) af[nxt][q] = lds_read_a(rd_off + a_rd[rd_kk] + q * 32 * 64);
+      if (q < NT)
+        bfr[nxt][q] = lds_read_b(rd_off + b_rd[q] + rd_kk * 16 * 512, rd_off + b_rd[q] + (rd_kk * 16 + 4) * 512);
 #pragma unroll
-      for (int mt = 0; mt < MT; mt++)
+      for (int i = 0; i < PER; i++) {
+        const int m = q * PER + i, mt = m / NT, nt = m % NT;
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mt], bfr[cur][nt], acc[mt][nt], 0, 0, 0);
+      }
+      const int n_reads = (q < MT ? 1 : 0) + (q < NT ? 2 : 0);
 #pragma unroll
-        for (int nt = 0; nt < NT; nt++)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][mt], bfr[buf][nt], acc[mt][nt], 0, 0, 0);
+      for (int i = 0; i < PER; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+#pragma unroll
+      for (int i = PER; i < 3; i++)
+        if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     };
-    // first half of a stage: fetch the fragments of its second half, multiply the first
-    auto half1 = [&](uint32_t so) {
+    auto half1 = [&](int stage_issue, bool do_issue, uint32_t so) {
 #pragma unroll
-      for (int mt = 0; mt < MT; mt++) af[1][mt] = lds_read_a(so + a_rd[1] + mt * 32 * 64);
-#pragma unroll
-      for (int nt = 0; nt < NT; nt++) bfr[1][nt] = lds_read_b(so + b_rd[nt] + 16 * 512, so + b_rd[nt] + 20 * 512);
-      mfma_all(0);
-      interleave_hint<N_READS, MT * NT>();
+      for (int q = 0; q < 4; q++) {
+        if (do_issue && q < LA) issue_a(stage_issue, q);
+        group(0, 1, so, 1, q);
+      }
     };
-    // second half: fetch the first fragments of the next stage, multiply the second half
-    auto half2 = [&](uint32_t sn) {
+    auto half2 = [&](int stage_issue, bool do_issue, uint32_t sn) {
 #pragma unroll
-      for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(sn + a_rd[0] + mt * 32 * 64);
-#pragma unroll
-      for (int nt = 0; nt < NT; nt++) bfr[0][nt] = lds_read_b(sn + b_rd[nt], sn + b_rd[nt] + 4 * 512);
-      mfma_all(1);
-      interleave_hint<N_READS, MT * NT>();
+      for (int q = 0; q < 4; q++) {
+        if (do_issue && q < LB) issue_b(stage_issue, q);
+        group(1, 0, sn, 0, q);
+      }
     };
 
-    const int nk = p.K / BK;  // >= NS (checked on the host)
+    const int nk = p.K / BK;  // >= NS - 1 (checked on the host)
 #pragma unroll
-    for (int s = 0; s < NS - 1; s++) issue(s);
+    for (int s = 0; s < NS - 1; s++) {
+#pragma unroll
+      for (int j = 0; j < LA; j++) issue_a(s, j);
+#pragma unroll
+      for (int j = 0; j < LB; j++) issue_b(s, j);
+      advance();
+    }
     wait_vmcnt<(NS - 2) * LS>();
     __syncthreads();
 #pragma unroll
@@ -302,25 +304,31 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
 
     int kt = 0;
     for (; kt < nk - (NS - 1); kt++) {
-      issue((kt + NS - 1) % NS);
-      half1((kt % NS) * STAGE);
-      // stage kt+1 has landed for this lane; after the barrier it has for all, and all are done reading stage kt
-      wait_vmcnt<(NS - 2) * LS>();
+      const int st = (kt + NS - 1) % NS;
+      half1(st, true, (kt % NS) * STAGE);
+      // stage kt+1 has landed for this lane (younger: stage kt+2 and the A rows of stage kt+3); after the barrier
+      // it has for all, and all are done reading stage kt
+      wait_vmcnt<LS + LA>();
       __syncthreads();
-      half2(((kt + 1) % NS) * STAGE);
+      half2(st, true, ((kt + 1) % NS) * STAGE);
+      advance();
     }
-    half1((kt % NS) * STAGE);
+    half1(0, false, (kt % NS) * STAGE);
     wait_vmcnt<LS>();
     __syncthreads();
-    half2(((kt + 1) % NS) * STAGE);
+    half2(0, false, ((kt + 1) % NS) * STAGE);
     kt++;
-    half1((kt % NS) * STAGE);
+    half1(0, false, (kt % NS) * STAGE);
     wait_vmcnt<0>();
     __syncthreads();
-    half2(((kt + 1) % NS) * STAGE);
+    half2(0, false, ((kt + 1) % NS) * STAGE);
     kt++;
-    half1((kt % NS) * STAGE);
-    mfma_all(1);
+    half1(0, false, (kt % NS) * STAGE);
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+      for (int nt = 0; nt < NT; nt++)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][mt], bfr[1][nt], acc[mt][nt], 0, 0, 0);
 
     // epilogue: lane holds column (lane & 31) of each 32x32 block, rows (i/4)*8 + (lane/32)*4 + i%4
     const int rbase = wm * (MT * 32) + (lane >> 5) * 4;
