@@ -63,7 +63,7 @@ int moe_plan_create(moe_plan_t **plan, const moe_shape_t *shape, const int32_t *
 int moe_plan_destroy(moe_plan_t *plan);
 
 /* Tunables.  Keys:
- *   "tile_m"       64 / 128 / 256: rows of a GroupGEMM tile (default: chosen from T*k/E)
+ *   "tile_m"       64 / 128 / 256: rows of the tallest GroupGEMM tile (default: chosen from T*k/E)
  *   "n_dm"         data-movement workgroups of the layer1 kernel (default: table lookup per shape)
  *   "layer1_order" 0 = expert-major tiles, separate combine kernel afterwards;
  *                  1 = column-panel-major tiles (Fig. 6), combine workgroups inside the GEMM kernel
@@ -119,11 +119,14 @@ int moe_layer_forward(moe_plan_t *plan, const void *x, const int32_t *topk_ids, 
 int moe_get_index_outputs(const moe_plan_t *plan, const void *workspace, int32_t *expert_counts,
                           int32_t *expert_offsets, int32_t *perm, int32_t *inv_perm, void *hip_stream);
 
-/* Tile table of the layer0 GroupGEMM as built by the last forward (dev pointers, each [max_tiles],
- * entries beyond *n_tiles untouched; n_tiles: dev int32 [1]): expert, first sorted row, rows, and
- * the source segment the tile waits for.  max_tiles >= moe_plan_max_tiles(plan). */
+/* Tile table of the GroupGEMMs as built by the last forward (dev pointers, each [max_tiles], any may be
+ * NULL, entries beyond *n_tiles untouched; n_tiles: dev int32 [1]): expert, first sorted row, rows, the
+ * source segment the tile waits for, and the height (64 / 128 / 256 rows) of the kernel variant that
+ * computes it.  An expert's rows are cut into tiles of "tile_m" rows; the remainder goes into shorter
+ * tiles so that little of a tile is padding.  max_tiles >= moe_plan_max_tiles(plan). */
 int moe_get_tile_table(const moe_plan_t *plan, const void *workspace, int32_t *n_tiles, int32_t *tile_expert,
-                       int32_t *tile_row0, int32_t *tile_rows, int32_t *tile_ready_seg, void *hip_stream);
+                       int32_t *tile_row0, int32_t *tile_rows, int32_t *tile_ready_seg, int32_t *tile_height,
+                       void *hip_stream);
 int32_t moe_plan_max_tiles(const moe_plan_t *plan);
 
 /* Average time in ms of the four phases (index build, layer0 kernel, layer1 kernel incl. fused combine,

@@ -70,7 +70,7 @@ def load_library():
     lib.moe_layer_forward.restype = C.c_int
     lib.moe_get_index_outputs.argtypes = [C.c_void_p, vp, i32p, i32p, i32p, i32p, vp]
     lib.moe_get_index_outputs.restype = C.c_int
-    lib.moe_get_tile_table.argtypes = [C.c_void_p, vp, i32p, i32p, i32p, i32p, i32p, vp]
+    lib.moe_get_tile_table.argtypes = [C.c_void_p, vp, i32p, i32p, i32p, i32p, i32p, i32p, vp]
     lib.moe_get_tile_table.restype = C.c_int
     lib.moe_last_device_status.argtypes = [C.c_void_p, vp, vp]
     lib.moe_last_device_status.restype = C.c_int
@@ -158,9 +158,10 @@ def moe_get_index_outputs(plan: int, workspace, expert_counts=None, expert_offse
 
 
 def moe_get_tile_table(plan: int, workspace, n_tiles, tile_expert, tile_row0, tile_rows, tile_ready_seg,
-                       stream=None) -> None:
+                       tile_height=None, stream=None) -> None:
     _check(load_library().moe_get_tile_table(plan, _ptr(workspace), _ptr(n_tiles), _ptr(tile_expert), _ptr(tile_row0),
-                                             _ptr(tile_rows), _ptr(tile_ready_seg), _stream(stream)),
+                                             _ptr(tile_rows), _ptr(tile_ready_seg), _ptr(tile_height),
+                                             _stream(stream)),
            "moe_get_tile_table")
 
 

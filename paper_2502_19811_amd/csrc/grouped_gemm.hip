@@ -22,6 +22,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 enum { MODE_L0_GELU = 0, MODE_L0_SWIGLU = 1, MODE_L1 = 2 };
 
@@ -56,17 +58,20 @@ __device__ __forceinline__ void wait_vmcnt() {
 // live accumulators.
 __device__ __forceinline__ float gelu_erf(float v) {
   const float z = fabsf(v) * 0.70710678118654752f;
-  const float t = 1.0f / (1.0f + 0.3275911f * z);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
   float poly = 1.061405429f;
   poly = poly * t - 1.453152027f;
   poly = poly * t + 1.421413741f;
   poly = poly * t - 0.284496736f;
   poly = poly * t + 0.254829592f;
-  const float erf_abs = 1.0f - poly * t * __expf(-z * z);
+  const float erf_abs = 1.0f - poly * t * __builtin_amdgcn_exp2f(z * z * -1.4426950408889634f);
   const float erf_v = v < 0.f ? -erf_abs : erf_abs;
   return 0.5f * v * (1.0f + erf_v);
 }
-__device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
+// v * sigmoid(v) with the hardware exp2 and reciprocal (about 1 ulp each; the result is rounded to bf16 anyway).
+__device__ __forceinline__ float silu(float v) {
+  return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f));
+}
 
 // Wait until *flag >= want.  Returns false if the spin limit (when set) ran out.
 __device__ __forceinline__ bool spin_until_ge(const uint32_t* flag, uint32_t want, uint32_t spin_limit) {
@@ -78,36 +83,88 @@ __device__ __forceinline__ bool spin_until_ge(const uint32_t* flag, uint32_t wan
   return true;
 }
 
-// Top-k weighted reduction of one unit: 32 tokens x one 256-column panel of Y.
-__device__ __forceinline__ void combine_unit(const GemmParams& p, int panel, int chunk) {
+// Top-k weighted reduction of one unit: kCombineChunk tokens x one 256-column panel of Y.  A thread owns 8 columns
+// (16 bytes) of every 8th token of the unit; the rows of several tokens are requested before any is used, because
+// with one workgroup per compute unit only loads in flight can cover the memory latency.
+template <int K>
+__device__ __forceinline__ void combine_unit_k(const GemmParams& p, int panel, int chunk, int k_runtime) {
+  constexpr int KK = K > 0 ? K : 1;
+  constexpr int TB = K == 0 ? 1 : (K <= 2 ? 8 : (K <= 4 ? 4 : 2));   // tokens in flight per thread
   const int tid = threadIdx.x;
-  const int cg = tid & 31;
+  const int cg = tid & 31, ts = tid >> 5;
+  const size_t col = (size_t)panel * BN + cg * 8;
+  const int k = K > 0 ? K : k_runtime;
+#pragma unroll 1
+  for (int i0 = 0; i0 < kCombineChunk / 8; i0 += TB) {
+    int t[TB];
+    float acc[TB][8];
 #pragma unroll
-  for (int i = 0; i < kCombineChunk / 8; i++) {
-    const int t = chunk * kCombineChunk + i * 8 + (tid >> 5);
-    if (t >= p.T) continue;
-    float acc[8];
+    for (int b = 0; b < TB; b++) {
+      t[b] = chunk * kCombineChunk + (i0 + b) * 8 + ts;
 #pragma unroll
-    for (int c = 0; c < 8; c++) acc[c] = 0.f;
-    const size_t col = (size_t)panel * BN + cg * 8;
-    for (int j = 0; j < p.k; j++) {
-      const int row = p.inv_perm[t * p.k + j];
-      const float w = p.topk_weights[t * p.k + j];
-      const u32x4 v = *(const u32x4*)(p.C + (size_t)row * p.ldc + col);
+      for (int c = 0; c < 8; c++) acc[b][c] = 0.f;
+    }
+    if (K > 0) {
+      int row[TB][KK];
+      float w[TB][KK];
+      u32x4 v[TB][KK];
 #pragma unroll
-      for (int c = 0; c < 4; c++) {
-        acc[2 * c] += w * __uint_as_float(v[c] << 16);
-        acc[2 * c + 1] += w * __uint_as_float(v[c] & 0xffff0000u);
+      for (int b = 0; b < TB; b++) {
+        const int tt = t[b] < p.T ? t[b] : p.T - 1;
+#pragma unroll
+        for (int j = 0; j < KK; j++) {
+          row[b][j] = p.inv_perm[tt * KK + j];
+          w[b][j] = p.topk_weights[tt * KK + j];
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < TB; b++)
+#pragma unroll
+        for (int j = 0; j < KK; j++) v[b][j] = *(const u32x4*)(p.C + (size_t)row[b][j] * p.ldc + col);
+#pragma unroll
+      for (int b = 0; b < TB; b++)
+#pragma unroll
+        for (int j = 0; j < KK; j++)
+#pragma unroll
+          for (int c = 0; c < 4; c++) {
+            acc[b][2 * c] += w[b][j] * __uint_as_float(v[b][j][c] << 16);
+            acc[b][2 * c + 1] += w[b][j] * __uint_as_float(v[b][j][c] & 0xffff0000u);
+          }
+    } else {
+      if (t[0] < p.T) {
+        for (int j = 0; j < k; j++) {
+          const int row = p.inv_perm[t[0] * k + j];
+          const float w = p.topk_weights[t[0] * k + j];
+          const u32x4 v = *(const u32x4*)(p.C + (size_t)row * p.ldc + col);
+#pragma unroll
+          for (int c = 0; c < 4; c++) {
+            acc[0][2 * c] += w * __uint_as_float(v[c] << 16);
+            acc[0][2 * c + 1] += w * __uint_as_float(v[c] & 0xffff0000u);
+          }
+        }
       }
     }
-    u32x4 o;
 #pragma unroll
-    for (int c = 0; c < 4; c++) {
-      typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-      bf16x2 pr = {(__bf16)acc[2 * c], (__bf16)acc[2 * c + 1]};
-      o[c] = __builtin_bit_cast(uint32_t, pr);
+    for (int b = 0; b < TB; b++) {
+      if (t[b] >= p.T) continue;
+      u32x4 o;
+#pragma unroll
+      for (int c = 0; c < 4; c++) {
+        bf16x2 pr = {(__bf16)acc[b][2 * c], (__bf16)acc[b][2 * c + 1]};
+        o[c] = __builtin_bit_cast(uint32_t, pr);
+      }
+      *(u32x4*)(p.out + (size_t)t[b] * p.H + col) = o;
     }
-    *(u32x4*)(p.out + (size_t)t * p.H + col) = o;
+  }
+}
+
+__device__ __forceinline__ void combine_unit(const GemmParams& p, int panel, int chunk) {
+  switch (p.k) {
+    case 1: combine_unit_k<1>(p, panel, chunk, 1); break;
+    case 2: combine_unit_k<2>(p, panel, chunk, 2); break;
+    case 4: combine_unit_k<4>(p, panel, chunk, 4); break;
+    case 8: combine_unit_k<8>(p, panel, chunk, 8); break;
+    default: combine_unit_k<0>(p, panel, chunk, p.k); break;
   }
 }
 
@@ -143,8 +200,33 @@ __device__ __forceinline__ void combine_loop(const GemmParams& p, int32_t* lds_s
   }
 }
 
+// Next position of XCD x's share of the schedule (positions x, x + 8, x + 16, ...); may lie past the end.
+__device__ __forceinline__ int take_from(const GemmParams& p, int x) {
+  return __hip_atomic_fetch_add(&p.queue_heads[x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * kXcds + x;
+}
+// Own share first, then the other XCDs' leftovers; -1 when the schedule is used up.
+__device__ __forceinline__ int take_any(const GemmParams& p, int xcd, int first_offset, int n_items) {
+  for (int d = first_offset; d < kXcds; d++) {
+    const int idx = take_from(p, (xcd + d) & (kXcds - 1));
+    if (idx < n_items) return idx;
+  }
+  return -1;
+}
+__device__ __forceinline__ void block_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Publishes one finished M-tile of column panel `panel` to the data-movement side: every wavefront makes its stores
+// visible device-wide, then one thread bumps the panel's counter.
+__device__ __forceinline__ void publish_panel(const GemmParams& p, int panel) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  __syncthreads();
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(&p.panel_done[panel], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One tile of BM = WM*MT*32 rows by 256 columns.  lds_slot[0] receives the schedule position this workgroup
+// works on next (fetched while this tile runs).
 template <int WM, int MT, int NT, int MODE>
-__global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
+__device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, int m_tile,
+                                         int n_tile, int xcd, int n_items, int& pending_panel) {
   constexpr int WN = 4 / WM;
   constexpr int BM = WM * MT * 32;
   static_assert(WN * NT * 32 == BN, "tile must be 256 columns wide");
@@ -154,20 +236,17 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   constexpr int LB = 4;        // B loads per lane per stage
   constexpr int LS = LA + LB;
 
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  __shared__ int32_t lds_slot;
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-  const int tid = threadIdx.x, lane = tid & 63;
+  // The thread index is made opaque per tile: otherwise the lane-dependent address constants of all three tile
+  // heights are hoisted out of the tile loop, kept live across it and spilled.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = w / WN, wn = w % WN;
   const int g = lane >> 4, j16 = lane & 15;
 
-  if (MODE == MODE_L1 && (int)blockIdx.x >= p.n_mfma) {
-    if (p.fused_combine) combine_loop(p, &lds_slot);
-    return;
-  }
-
-  // LDS read addresses (stage 0), constant over the kernel
+  // LDS read addresses (stage 0)
   uint32_t a_rd[2], b_rd[NT];
   {
     const int r = wm * (MT * 32) + (lane & 31);
@@ -180,27 +259,10 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     for (int nt = 0; nt < NT; nt++)
       b_rd[nt] = lds0 + A_STAGE + krow * 512 + (((wn * NT + nt) ^ swz) << 6) + (16 * (g & 1) + 4 * (j16 & 3)) * 2;
   }
-
-  const int n_items = *p.n_items;
-  for (int item = blockIdx.x; item < n_items; item += p.n_mfma) {
-    const uint32_t it = p.items[item];
-    const int m_tile = it >> 12, n_tile = it & 0xfff;
+  {
     const int expert = p.tile_expert[m_tile];
     const int row0 = p.tile_row0[m_tile];
     const int nrows = p.tile_rows[m_tile];
-
-    // every wavefront must be done with the LDS stages of the previous tile before they are refilled
-    __syncthreads();
-    if (MODE != MODE_L1 && p.seg_ready != nullptr) {
-      if (tid == 0) {
-        const bool ok = spin_until_ge(&p.seg_ready[p.tile_ready[m_tile]], p.ready_epoch, p.spin_limit);
-        if (!ok) atomicExch(p.status, (int)MOE_ERR_TIMEOUT);
-        lds_slot = ok;
-      }
-      __syncthreads();
-      if (!lds_slot) continue;
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
-    }
 
     // per-lane global offsets of the loads of one stage
     uint32_t aoff[LA], boff[LB];
@@ -259,7 +321,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
 #pragma unroll
       for (int i = 0; i < PER; i++) {
         const int m = q * PER + i, mt = m / NT, nt = m % NT;
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mt], bfr[cur][nt], acc[mt][nt], 0, 0, 0);
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][nt], af[cur][mt], acc[mt][nt], 0, 0, 0);
       }
       const int n_reads = (q < MT ? 1 : 0) + (q < NT ? 2 : 0);
 #pragma unroll
@@ -286,6 +348,14 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
       }
     };
 
+    // The next schedule position is requested after the row indices have been read and before this tile's loads are
+    // issued: the atomic is then the oldest outstanding memory operation of the wavefront, so it neither delays the
+    // address set-up nor disturbs the load counts waited for below.
+    asm volatile("" ::: "memory");
+    int next_idx = 0;
+    if (tid == 0) next_idx = take_from(p, xcd);
+    asm volatile("" ::: "memory");
+
     const int nk = p.K / BK;  // >= NS - 1 (checked on the host)
 #pragma unroll
     for (int s = 0; s < NS - 1; s++) {
@@ -296,7 +366,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
       advance();
     }
     wait_vmcnt<(NS - 2) * LS>();
-    __syncthreads();
+    block_barrier();
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(a_rd[0] + mt * 32 * 64);
 #pragma unroll
@@ -309,18 +379,18 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
       // stage kt+1 has landed for this lane (younger: stage kt+2 and the A rows of stage kt+3); after the barrier
       // it has for all, and all are done reading stage kt
       wait_vmcnt<LS + LA>();
-      __syncthreads();
+      block_barrier();
       half2(st, true, ((kt + 1) % NS) * STAGE);
       advance();
     }
     half1(0, false, (kt % NS) * STAGE);
     wait_vmcnt<LS>();
-    __syncthreads();
+    block_barrier();
     half2(0, false, ((kt + 1) % NS) * STAGE);
     kt++;
     half1(0, false, (kt % NS) * STAGE);
     wait_vmcnt<0>();
-    __syncthreads();
+    block_barrier();
     half2(0, false, ((kt + 1) % NS) * STAGE);
     kt++;
     half1(0, false, (kt % NS) * STAGE);
@@ -328,57 +398,130 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
       for (int nt = 0; nt < NT; nt++)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][mt], bfr[1][nt], acc[mt][nt], 0, 0, 0);
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[1][nt], af[1][mt], acc[mt][nt], 0, 0, 0);
 
-    // epilogue: lane holds column (lane & 31) of each 32x32 block, rows (i/4)*8 + (lane/32)*4 + i%4
-    const int rbase = wm * (MT * 32) + (lane >> 5) * 4;
-    if (MODE == MODE_L0_SWIGLU) {
-      const int f0 = col0 + wn * (NT * 16) + (lane & 31);
+    // hand the next schedule position to the whole workgroup (read after the barrier at the top of the tile loop)
+    if (tid == 0) {
+      if (next_idx >= n_items) next_idx = take_any(p, xcd, 1, n_items);
+      lds_slot[0] = next_idx;
+    }
+
+    // Epilogue.  The MFMAs ran with the operands swapped (B fragment first), so a lane holds, for output row
+    // lane & 31 of each 32x32 block, the columns 8*(i/4) + 4*(lane/32) + i%4: four consecutive columns per group of
+    // four accumulator registers.  The wavefront's part of the tile is staged in LDS as bf16 (8-byte writes, 16-byte
+    // chunks XOR-swizzled by row) and written out in full 16-byte pieces, whole rows at a time; 2-byte stores straight
+    // from the accumulators cost a tenth of the tile's time.
+    constexpr int OUT_NT = (MODE == MODE_L0_SWIGLU) ? NT / 2 : NT;   // 32-column blocks of output per wavefront
+    constexpr int RB = OUT_NT * 64;                                   // bytes per staged row
+    constexpr int NC = RB / 16;                                       // 16-byte chunks per staged row
+    constexpr int RPB = RB >= 256 ? 1 : 256 / RB;                     // rows per 256 bytes of LDS banks
+    // The previous tile is published only now: its stores have drained during this tile's main loop, so the release
+    // does not wait for them (publishing right after the stores would stall the next tile behind the store burst).
+    if (MODE == MODE_L1 && pending_panel >= 0) {
+      publish_panel(p, pending_panel);
+      pending_panel = -1;
+    }
+    block_barrier();   // every wavefront is done reading the operand stages
+    const uint32_t cbase = lds0 + w * (MT * 32 * RB);
+    int lane_e = lane;   // opaque again: the epilogue's addresses are computed here, not before the main loop
+    asm volatile("" : "+v"(lane_e));
+    {
+      const int m_in = lane_e & 31, half = lane_e >> 5;
 #pragma unroll
-      for (int mt = 0; mt < MT; mt++)
+      for (int mt = 0; mt < MT; mt++) {
+        const int m = mt * 32 + m_in;
+        const uint32_t row_addr = cbase + m * RB + half * 8;
+        const int sw = (m / RPB) & (NC - 1);
 #pragma unroll
-        for (int nt = 0; nt < NT / 2; nt++)
+        for (int nt = 0; nt < OUT_NT; nt++) {
+          if (MODE == MODE_L0_GELU) __builtin_amdgcn_sched_barrier(0);  // bounds the live activation temporaries
 #pragma unroll
-          for (int i = 0; i < 16; i++) {
-            const int r = rbase + mt * 32 + (i >> 2) * 8 + (i & 3);
-            if (r < nrows) {
-              const float hval = silu(acc[mt][nt][i]) * acc[mt][nt + NT / 2][i];
-              ((__bf16*)p.C)[(size_t)(row0 + r) * p.ldc + f0 + nt * 32] = (__bf16)hval;
+          for (int q = 0; q < 4; q++) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+              if (MODE == MODE_L0_SWIGLU) v[i] = silu(acc[mt][nt][q * 4 + i]) * acc[mt][nt + NT / 2][q * 4 + i];
+              else if (MODE == MODE_L0_GELU) v[i] = gelu_erf(acc[mt][nt][q * 4 + i]);
+              else v[i] = acc[mt][nt][q * 4 + i];
             }
-          }
-    } else {
-      const int c0 = col0 + wn * (NT * 32) + (lane & 31);
-#pragma unroll
-      for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-          __builtin_amdgcn_sched_barrier(0);  // keeps the activation temporaries of one block live at a time
-#pragma unroll
-          for (int i = 0; i < 16; i++) {
-            const int r = rbase + mt * 32 + (i >> 2) * 8 + (i & 3);
-            if (r < nrows) {
-              float v = acc[mt][nt][i];
-              if (MODE == MODE_L0_GELU) v = gelu_erf(v);
-              ((__bf16*)p.C)[(size_t)(row0 + r) * p.ldc + c0 + nt * 32] = (__bf16)v;
-            }
+            bf16x2 lo = {(__bf16)v[0], (__bf16)v[1]}, hi = {(__bf16)v[2], (__bf16)v[3]};
+            u32x2 pk = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+            const int chunk = nt * 4 + q;
+            *(u32x2 __attribute__((address_space(3)))*)(uintptr_t)(row_addr + ((chunk ^ sw) << 4)) = pk;
           }
         }
+      }
     }
-    if (MODE == MODE_L1) {
-      // publish: this M-tile of column panel n_tile is in memory
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-      __syncthreads();
-      if (tid == 0) __hip_atomic_fetch_add(&p.panel_done[n_tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    {
+      const int col_base = (MODE == MODE_L0_SWIGLU) ? col0 + wn * (NT * 16) : col0 + wn * (NT * 32);
+      const int c = lane_e % NC;
+#pragma unroll
+      for (int it = 0; it < MT * 32 * NC / 64; it++) {
+        const int r = it * (64 / NC) + lane_e / NC;
+        const u32x4 v = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
+            cbase + r * RB + ((c ^ ((r / RPB) & (NC - 1))) << 4));
+        const int grow = wm * (MT * 32) + r;
+        if (grow < nrows) *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v;
+      }
     }
+    if (MODE == MODE_L1 && p.fused_combine) pending_panel = n_tile;
   }
-  if (MODE == MODE_L1 && p.fused_combine) combine_loop(p, &lds_slot);
 }
 
-template <int WM, int MT, int NT, int MODE>
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int32_t lds_slot[2];
+  const int tid = threadIdx.x;
+  if (MODE == MODE_L1 && (int)blockIdx.x >= p.n_mfma) {
+    if (p.fused_combine) combine_loop(p, &lds_slot[1]);
+    return;
+  }
+  const int xcd = blockIdx.x & (kXcds - 1);
+  const int n_items = *p.n_items;
+  int pending_panel = -1;   // layer1: column panel of the last finished tile, not yet published
+  if (tid == 0) lds_slot[0] = take_any(p, xcd, 0, n_items);
+  while (true) {
+    // also: every wavefront is done with the LDS stages of the previous tile before they are refilled
+    __syncthreads();
+    const int idx = lds_slot[0];
+    __syncthreads();
+    if (idx < 0) break;
+    const uint32_t it = p.items[idx];
+    if (it == 0xffffffffu) {   // a hole of the schedule
+      if (tid == 0) lds_slot[0] = take_any(p, xcd, 0, n_items);
+      continue;
+    }
+    const int m_tile = it >> 12, n_tile = it & 0xfff;
+    if (MODE != MODE_L1 && p.seg_ready != nullptr) {
+      if (tid == 0) {
+        const bool ok = spin_until_ge(&p.seg_ready[p.tile_ready[m_tile]], p.ready_epoch, p.spin_limit);
+        if (!ok) {
+          atomicExch(p.status, (int)MOE_ERR_TIMEOUT);
+          lds_slot[0] = take_any(p, xcd, 0, n_items);   // skip this tile
+        }
+        lds_slot[1] = ok;
+      }
+      __syncthreads();
+      if (!lds_slot[1]) continue;
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+    }
+    const int kind = p.tile_kind[m_tile];
+    if (kind == 2)
+      run_tile<2, 4, 4, MODE>(p, smem, lds_slot, m_tile, n_tile, xcd, n_items, pending_panel);
+    else if (kind == 1)
+      run_tile<2, 2, 4, MODE>(p, smem, lds_slot, m_tile, n_tile, xcd, n_items, pending_panel);
+    else
+      run_tile<1, 2, 2, MODE>(p, smem, lds_slot, m_tile, n_tile, xcd, n_items, pending_panel);
+  }
+  if (MODE == MODE_L1 && pending_panel >= 0) publish_panel(p, pending_panel);
+  if (MODE == MODE_L1 && p.fused_combine) combine_loop(p, &lds_slot[1]);
+}
+
+template <int MODE>
 static hipError_t launch_gemm(const GemmParams& p, int grid, hipStream_t st) {
-  constexpr int BM = WM * MT * 32;
-  constexpr int lds = NS * (BM * BK * 2 + B_STAGE);
-  auto kern = k_group_gemm<WM, MT, NT, MODE>;
+  constexpr int lds = NS * (256 * BK * 2 + B_STAGE);
+  auto kern = k_group_gemm<MODE>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -389,22 +532,12 @@ static hipError_t launch_gemm(const GemmParams& p, int grid, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_layer0(const GemmParams& p, int tile_m, int act, int grid, hipStream_t st) {
-  if (act == MOE_ACT_SWIGLU) {
-    if (tile_m == 256) return launch_gemm<2, 4, 4, MODE_L0_SWIGLU>(p, grid, st);
-    if (tile_m == 128) return launch_gemm<2, 2, 4, MODE_L0_SWIGLU>(p, grid, st);
-    return launch_gemm<1, 2, 2, MODE_L0_SWIGLU>(p, grid, st);
-  }
-  if (tile_m == 256) return launch_gemm<2, 4, 4, MODE_L0_GELU>(p, grid, st);
-  if (tile_m == 128) return launch_gemm<2, 2, 4, MODE_L0_GELU>(p, grid, st);
-  return launch_gemm<1, 2, 2, MODE_L0_GELU>(p, grid, st);
+hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st) {
+  if (act == MOE_ACT_SWIGLU) return launch_gemm<MODE_L0_SWIGLU>(p, grid, st);
+  return launch_gemm<MODE_L0_GELU>(p, grid, st);
 }
 
-hipError_t launch_layer1(const GemmParams& p, int tile_m, int grid, hipStream_t st) {
-  if (tile_m == 256) return launch_gemm<2, 4, 4, MODE_L1>(p, grid, st);
-  if (tile_m == 128) return launch_gemm<2, 2, 4, MODE_L1>(p, grid, st);
-  return launch_gemm<1, 2, 2, MODE_L1>(p, grid, st);
-}
+hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st) { return launch_gemm<MODE_L1>(p, grid, st); }
 
 // ---------------------------------------------------------------------------------------------
 // Stand-alone top-k weighted reduction (used when the layer1 kernel runs without data-movement workgroups).
@@ -431,7 +564,6 @@ __global__ __launch_bounds__(256) void k_combine(CombineParams p) {
     u32x4 o;
 #pragma unroll
     for (int c = 0; c < 4; c++) {
-      typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
       bf16x2 pr = {(__bf16)acc[2 * c], (__bf16)acc[2 * c + 1]};
       o[c] = __builtin_bit_cast(uint32_t, pr);
     }

@@ -83,7 +83,22 @@ __global__ __launch_bounds__(256) void k_index_hist(IndexParams p) {
 // ---------------------------------------------------------------------------------------------
 // Step 2 (one workgroup): expert counts and offsets, per-workgroup bases, the M-tile table, and
 // the counters of this forward reset to zero.
+//
+// Tiling of an expert's rows: as many tiles of tile_m rows as fit, then the remainder is cut so that little
+// of a tile is padding: with tile_m = 256 a remainder of up to 64 rows becomes one 64-row tile, up to 128 one
+// 128-row tile, up to 192 a 128-row and a 64-row tile, more one ragged 256-row tile (tile_m = 128: 64 or 128).
 // ---------------------------------------------------------------------------------------------
+__device__ inline int tail_tiles(int rem, int tile_m, int* h0, int* h1) {
+  // heights (kernel variant) of the tiles that cover a remainder of rem rows; returns their number (0..2)
+  if (rem == 0) return 0;
+  if (tile_m == 64) { *h0 = 64; return 1; }
+  if (rem <= 64) { *h0 = 64; return 1; }
+  if (rem <= 128 || tile_m == 128) { *h0 = 128; return 1; }
+  if (rem <= 192) { *h0 = 128; *h1 = 64; return 2; }
+  *h0 = 256;
+  return 1;
+}
+
 __global__ __launch_bounds__(256) void k_index_scan(IndexParams p) {
   __shared__ int32_t cnt[kMaxExperts];
   __shared__ int32_t off[kMaxExperts + 1];
@@ -105,7 +120,8 @@ __global__ __launch_bounds__(256) void k_index_scan(IndexParams p) {
       off[e] = o;
       tbase[e] = tb;
       o += cnt[e];
-      tb += (cnt[e] + p.tile_m - 1) / p.tile_m;
+      int h0 = 0, h1 = 0;
+      tb += cnt[e] / p.tile_m + tail_tiles(cnt[e] % p.tile_m, p.tile_m, &h0, &h1);
     }
     off[E] = o;
     tbase[E] = tb;
@@ -114,21 +130,33 @@ __global__ __launch_bounds__(256) void k_index_scan(IndexParams p) {
     p.ws.status[2] = tb * p.n_tiles_n0;
     p.ws.status[3] = tb * p.n_tiles_n1;
     p.ws.status[4] = 0;
-    p.ws.status[5] = 0;
-    p.ws.status[6] = 0;
   }
+  if (threadIdx.x < 2 * kXcds) p.ws.status[8 + threadIdx.x] = 0;
   for (int i = threadIdx.x; i < p.n_tiles_n1; i += 256) p.ws.panel_done[i] = 0;
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += 256) {
     p.ws.counts[e] = cnt[e];
     p.ws.offsets[e] = off[e];
-    int nt = tbase[e + 1] - tbase[e];
-    for (int i = 0; i < nt; i++) {
-      int ti = tbase[e] + i;
+    const int kind_full = p.tile_m == 256 ? 2 : (p.tile_m == 128 ? 1 : 0);
+    const int nfull = cnt[e] / p.tile_m;
+    int ti = tbase[e], row = off[e];
+    for (int i = 0; i < nfull; i++, ti++, row += p.tile_m) {
       p.ws.tile_expert[ti] = e;
-      p.ws.tile_row0[ti] = off[e] + i * p.tile_m;
-      int left = cnt[e] - i * p.tile_m;
-      p.ws.tile_rows[ti] = left < p.tile_m ? left : p.tile_m;
+      p.ws.tile_row0[ti] = row;
+      p.ws.tile_rows[ti] = p.tile_m;
+      p.ws.tile_kind[ti] = kind_full;
+    }
+    int h[2] = {0, 0};
+    const int nt = tail_tiles(cnt[e] % p.tile_m, p.tile_m, &h[0], &h[1]);
+    int left = cnt[e] % p.tile_m;
+    for (int i = 0; i < nt; i++, ti++) {
+      const int rows = left < h[i] ? left : h[i];
+      p.ws.tile_expert[ti] = e;
+      p.ws.tile_row0[ti] = row;
+      p.ws.tile_rows[ti] = rows;
+      p.ws.tile_kind[ti] = h[i] == 256 ? 2 : (h[i] == 128 ? 1 : 0);
+      row += rows;
+      left -= rows;
     }
   }
   if (threadIdx.x == 0) p.ws.offsets[E] = off[E];
@@ -197,89 +225,161 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
 // A tile can start once all its rows have arrived (Section 2.2.1); its rows are in source order, so that is
 // the segment of its last row.
 //
-// Layer0 schedule: order 0 keeps all M-tiles of one expert together while sweeping groups of 8 column
-// tiles, so that the workgroups running at the same time share weight panels (consecutive items go to
-// consecutive XCDs, which therefore keep to their own column tiles); order 1 lists the tiles by the segment
-// they wait for (Fig. 5: local and early-arriving rows first).
-// Layer1 schedule: order 1 is column-panel-major over all experts (Fig. 6) in groups of 8 panels, one per XCD;
-// order 0 is expert-major like layer0.
+// A schedule is a list of (M-tile, column tile) items.  Position i of the list belongs to XCD i % 8 (a
+// workgroup takes the next position of its own XCD's share and, when that is used up, of the others'), so
+// consecutive positions should differ in the column tile and keep the M-tile: the workgroups of one XCD then
+// work on few column tiles of many M-tiles and share weight panels in their L2.  Tall tiles come first and the
+// short tiles of the ragged ends last, so that the short ones fill the gaps at the end of the kernel.
+// Layer0, order 0: per tile height, experts in order; inside an expert groups of 8 column tiles, the expert's
+// M-tiles, the 8 column tiles.  Order 1: per tile height, M-tiles by the segment they wait for (Fig. 5: rows that
+// are local or arrive early first), all column tiles of an M-tile in a row.
+// Layer1: per tile height, the M-tiles are dealt to the XCDs in contiguous chunks and every XCD sweeps its chunk
+// column-panel-major, 4 panels at a time (Fig. 6).
 // ---------------------------------------------------------------------------------------------
-__device__ inline void emit_expert_major(uint32_t* items, const int32_t* tile_expert, int n_tiles, int n_tiles_n,
-                                         int tid, int nthreads) {
-  // Position of item (m, n): experts in order; inside an expert, groups of 8 column tiles; inside a group,
-  // M-tiles of the expert; inside an M-tile the 8 column tiles.  The tile table is expert-major, so the M-tiles
-  // of an expert are the consecutive range [m_lo, m_hi).
-  for (int m = tid; m < n_tiles; m += nthreads) {
-    const int e = tile_expert[m];
-    int m_lo = m, m_hi = m + 1;
-    while (m_lo > 0 && tile_expert[m_lo - 1] == e) m_lo--;
-    while (m_hi < n_tiles && tile_expert[m_hi] == e) m_hi++;
-    const int cnt = m_hi - m_lo;
-    const int ebase = m_lo * n_tiles_n;
-    for (int n = 0; n < n_tiles_n; n++) {
-      const int g = n >> 3, gw = min(8, n_tiles_n - g * 8);
-      const int pos = ebase + g * 8 * cnt + (m - m_lo) * gw + (n & 7);
-      items[pos] = pack_item(m, n);
-    }
+constexpr int kTileCap = 4096;  // tiles whose table fits the LDS copies of the schedule builder
+
+// Layer0 items of the tiles order[lo..hi) (one height, expert-major), written from position base on.
+// ord / exp_of: LDS copies (or the global arrays when the table is too large).
+template <typename OrdT, typename ExpT>
+__device__ inline void emit_expert_major(uint32_t* items, const OrdT* ord, const ExpT* exp_of, int lo, int hi, int base,
+                                         int n_tiles_n, int tid, int nthreads) {
+  // one (tile, group of 8 column tiles) pair per thread step
+  const int n_groups = (n_tiles_n + 7) >> 3;
+  for (int w = tid; w < (hi - lo) * n_groups; w += nthreads) {
+    const int i = lo + w / n_groups, g = w % n_groups;
+    const int e = exp_of[ord[i]];
+    int a = i, b = i + 1;
+    while (a > lo && exp_of[ord[a - 1]] == e) a--;
+    while (b < hi && exp_of[ord[b]] == e) b++;
+    const int cnt = b - a;
+    const int gw = min(8, n_tiles_n - g * 8);
+    const int pos = base + (a - lo) * n_tiles_n + g * 8 * cnt + (i - a) * gw;
+    for (int n = 0; n < gw; n++) items[pos + n] = pack_item(ord[i], g * 8 + n);
+  }
+}
+
+// Layer1 items of the tiles order[lo..hi): the tiles are dealt to the XCDs in contiguous chunks (an XCD then
+// keeps to few experts); XCD x's sequence is, per group of 4 column panels, its tiles, each with the 4 panels,
+// and sits at list positions seq * 8 + x from sequence index seq_base on.  Panel groups ascend, so all M-tiles
+// finish panel group g before g + 1 (Fig. 6).  Unused positions keep the no-op marker.
+template <typename OrdT>
+__device__ inline void emit_chunked(uint32_t* items, const OrdT* ord, int lo, int hi, int seq_base, int n_tiles_n,
+                                    int tid, int nthreads) {
+  const int nt = hi - lo;
+  const int chunk = (nt + kXcds - 1) / kXcds;
+  const int n_groups = (n_tiles_n + 3) >> 2;
+  for (int w = tid; w < nt * n_groups; w += nthreads) {
+    const int i = w / n_groups, g = w % n_groups;
+    const int x = i / chunk, j = i % chunk;
+    const int cnt = min(chunk, nt - x * chunk);
+    const int gw = min(4, n_tiles_n - g * 4);
+    const int seq = seq_base + g * 4 * cnt + j * gw;
+    for (int n = 0; n < gw; n++) items[(seq + n) * kXcds + x] = pack_item(ord[lo + i], g * 4 + n);
   }
 }
 
 __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
-  __shared__ int32_t seg_first[kMaxSegments + 1];  // first position of each ready-segment bucket
-  __shared__ int32_t seg_fill[kMaxSegments];
+  __shared__ int32_t cls_first[4];  // first position in order[] of the tiles of kind 2, 1, 0, and the end
+  __shared__ int32_t key_pos[3 * kMaxSegments];
+  __shared__ uint8_t keys[kTileCap];
+  __shared__ uint8_t exp_lds[kTileCap];
+  __shared__ uint16_t ord_lds[kTileCap];
   const int n_tiles = p.ws.status[1];
   const int tid = threadIdx.x;
-  const int S = p.s.S, k = p.s.k;
-  if (tid <= kMaxSegments) seg_first[tid] = 0;
-  if (tid < kMaxSegments) seg_fill[tid] = 0;
-  __syncthreads();
+  const int S = p.s.S;
+  const bool in_lds = n_tiles <= kTileCap;
+  const int nseg = p.layer0_order == 1 ? S : 1;
+  const int nkeys = 3 * nseg;
+  // the source segment each tile waits for; sort key = (height class, segment) or the height class alone
   for (int m = tid; m < n_tiles; m += 1024) {
     const int last = p.ws.tile_row0[m] + p.ws.tile_rows[m] - 1;
     const int t = p.ws.row_token[last];
     int s = 0;
     while (s + 1 < S && p.seg_offsets[s + 1] <= t) s++;
     p.ws.tile_ready[m] = s;
+    if (in_lds) {
+      keys[m] = (uint8_t)((2 - p.ws.tile_kind[m]) * nseg + (nseg > 1 ? s : 0));
+      exp_lds[m] = (uint8_t)p.ws.tile_expert[m];
+    }
+  }
+  // layer1 list: no-op markers everywhere first (its holes stay that way)
+  const int n_items1_cap = (n_tiles + 3 * kXcds) * p.n_tiles_n1;
+  for (int i = tid; i < n_items1_cap; i += 1024) p.ws.items1[i] = 0xffffffffu;
+  __syncthreads();
+  auto key_of = [&](int m) {
+    return in_lds ? (int)keys[m] : (2 - p.ws.tile_kind[m]) * nseg + (nseg > 1 ? p.ws.tile_ready[m] : 0);
+  };
+  // stable counting sort: one thread per key value walks the keys twice, first counting, then placing
+  if (tid < nkeys) {
+    int c = 0;
+    for (int m = 0; m < n_tiles; m++) c += (key_of(m) == tid);
+    key_pos[tid] = c;
   }
   __syncthreads();
-  // layer0
-  if (p.layer0_order == 0) {
-    emit_expert_major(p.ws.items0, p.ws.tile_expert, n_tiles, p.n_tiles_n0, tid, 1024);
-  } else {
-    // stable bucket sort of the M-tiles by ready segment (one thread: a few hundred tiles at most per bucket
-    // pass), then all column tiles of one M-tile in a row
-    if (tid == 0) {
-      for (int m = 0; m < n_tiles; m++) seg_first[p.ws.tile_ready[m] + 1]++;
-      for (int s = 0; s < S; s++) seg_first[s + 1] += seg_first[s];
+  if (tid == 0) {
+    int pos = 0;
+    for (int i = 0; i < nkeys; i++) {
+      if (i % nseg == 0) cls_first[i / nseg] = pos;
+      const int c = key_pos[i];
+      key_pos[i] = pos;
+      pos += c;
     }
-    __syncthreads();
-    if (tid == 0) {
-      for (int m = 0; m < n_tiles; m++) {
-        const int s = p.ws.tile_ready[m];
-        const int slot = seg_first[s] + seg_fill[s]++;
-        p.ws.items1[slot] = m;  // scratch: M-tiles in segment order
+    cls_first[3] = pos;
+  }
+  __syncthreads();
+  if (tid < nkeys) {
+    int pos = key_pos[tid];
+    for (int m = 0; m < n_tiles; m++)
+      if (key_of(m) == tid) {
+        if (in_lds) ord_lds[pos] = (uint16_t)m; else p.ws.tile_order[pos] = m;
+        pos++;
+      }
+  }
+  __syncthreads();
+  for (int c = 0; c < 3; c++) {
+    const int lo = cls_first[c], hi = cls_first[c + 1];
+    if (p.layer0_order == 0) {
+      if (in_lds) emit_expert_major(p.ws.items0, ord_lds, exp_lds, lo, hi, lo * p.n_tiles_n0, p.n_tiles_n0, tid, 1024);
+      else emit_expert_major(p.ws.items0, p.ws.tile_order, p.ws.tile_expert, lo, hi, lo * p.n_tiles_n0, p.n_tiles_n0, tid, 1024);
+    } else {
+      for (int i = tid; i < (hi - lo) * p.n_tiles_n0; i += 1024) {
+        const int m = in_lds ? (int)ord_lds[lo + i / p.n_tiles_n0] : p.ws.tile_order[lo + i / p.n_tiles_n0];
+        p.ws.items0[lo * p.n_tiles_n0 + i] = pack_item(m, i % p.n_tiles_n0);
       }
     }
+  }
+  if (p.layer0_order == 1) {
+    // layer1 wants table order inside a height: rebuild order[] (the layer0 list is complete by now)
     __syncthreads();
-    for (int i = tid; i < n_tiles * p.n_tiles_n0; i += 1024) {
-      const int slot = i / p.n_tiles_n0, n = i % p.n_tiles_n0;
-      p.ws.items0[i] = pack_item(p.ws.items1[slot], n);
+    if (tid < 3) {
+      int pos = cls_first[tid];
+      for (int m = 0; m < n_tiles; m++)
+        if (key_of(m) / nseg == tid) {
+          if (in_lds) ord_lds[pos] = (uint16_t)m; else p.ws.tile_order[pos] = m;
+          pos++;
+        }
     }
     __syncthreads();
   }
-  // layer1
-  if (p.layer1_order == 0) {
-    emit_expert_major(p.ws.items1, p.ws.tile_expert, n_tiles, p.n_tiles_n1, tid, 1024);
-  } else {
-    const int total = n_tiles * p.n_tiles_n1;
-    for (int i = tid; i < total; i += 1024) {
-      // groups of 8 panels; inside a group M-tile-major, the 8 panels of one M-tile in a row
-      const int per_group = n_tiles * 8;
-      const int g = i / per_group, r = i % per_group;
-      const int gw = min(8, p.n_tiles_n1 - g * 8);
-      const int m = r / gw, n = g * 8 + r % gw;
-      p.ws.items1[i] = pack_item(m, n);
-    }
+  int seq_base = 0;
+  for (int c = 0; c < 3; c++) {
+    const int lo = cls_first[c], hi = cls_first[c + 1];
+    if (in_lds) emit_chunked(p.ws.items1, ord_lds, lo, hi, seq_base, p.n_tiles_n1, tid, 1024);
+    else emit_chunked(p.ws.items1, p.ws.tile_order, lo, hi, seq_base, p.n_tiles_n1, tid, 1024);
+    seq_base += (hi - lo + kXcds - 1) / kXcds * p.n_tiles_n1;
   }
+  if (tid == 0) p.ws.status[3] = seq_base * kXcds;   // length of the layer1 list including its holes
+}
+
+__global__ void k_tile_heights(const int32_t* __restrict__ kind, int32_t* __restrict__ height, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) height[i] = 64 << kind[i];
+}
+
+hipError_t launch_tile_heights(const int32_t* kind, int32_t* height, int n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_tile_heights, dim3((n + 255) / 256), dim3(256), 0, st, kind, height, n);
+  return hipGetLastError();
 }
 
 hipError_t launch_index_build(const IndexParams& p, hipStream_t st) {

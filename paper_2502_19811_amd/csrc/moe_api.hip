@@ -29,7 +29,7 @@ struct moe_plan {
   int32_t max_tiles;
   int32_t n_tiles_n0, n_tiles_n1;
   size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
-      off_tile_row0, off_tile_rows, off_tile_ready, off_items0, off_items1, off_panel_done, off_h, off_Y, total_bytes;
+      off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_h, off_Y, total_bytes;
 };
 
 namespace {
@@ -40,7 +40,7 @@ void layout(moe_plan* p) {
   const Shape& s = p->s;
   p->n_index_blocks = (s.R + kIndexChunk - 1) / kIndexChunk;
   if (p->n_index_blocks < 1) p->n_index_blocks = 1;
-  p->max_tiles = s.R / p->tile_m + s.E;
+  p->max_tiles = s.R / p->tile_m + 2 * s.E;
   p->n_tiles_n0 = s.act == MOE_ACT_SWIGLU ? s.F / (kTileN / 2) : s.F / kTileN;
   p->n_tiles_n1 = s.H / kTileN;
   size_t o = 0;
@@ -49,7 +49,7 @@ void layout(moe_plan* p) {
     o = align_up(o + bytes, 256);
     return at;
   };
-  p->off_status = take(16 * 4);
+  p->off_status = take(64 * 4);
   p->off_counts = take((size_t)s.E * 4);
   p->off_offsets = take((size_t)(s.E + 1) * 4);
   p->off_perm = take((size_t)s.R * 4);
@@ -60,8 +60,10 @@ void layout(moe_plan* p) {
   p->off_tile_row0 = take((size_t)p->max_tiles * 4);
   p->off_tile_rows = take((size_t)p->max_tiles * 4);
   p->off_tile_ready = take((size_t)p->max_tiles * 4);
+  p->off_tile_kind = take((size_t)p->max_tiles * 4);
+  p->off_tile_order = take((size_t)p->max_tiles * 4);
   p->off_items0 = take((size_t)p->max_tiles * p->n_tiles_n0 * 4);
-  p->off_items1 = take((size_t)p->max_tiles * p->n_tiles_n1 * 4);
+  p->off_items1 = take((size_t)(p->max_tiles + 3 * kXcds) * p->n_tiles_n1 * 4);
   p->off_panel_done = take((size_t)p->n_tiles_n1 * 4);
   p->off_h = take((size_t)s.R * s.F * 2);
   p->off_Y = take((size_t)s.R * s.H * 2);
@@ -82,6 +84,8 @@ Workspace view(const moe_plan* p, void* base) {
   w.tile_row0 = (int32_t*)(b + p->off_tile_row0);
   w.tile_rows = (int32_t*)(b + p->off_tile_rows);
   w.tile_ready = (int32_t*)(b + p->off_tile_ready);
+  w.tile_kind = (int32_t*)(b + p->off_tile_kind);
+  w.tile_order = (int32_t*)(b + p->off_tile_order);
   w.items0 = (uint32_t*)(b + p->off_items0);
   w.items1 = (uint32_t*)(b + p->off_items1);
   w.panel_done = (uint32_t*)(b + p->off_panel_done);
@@ -91,9 +95,10 @@ Workspace view(const moe_plan* p, void* base) {
 }
 
 int default_tile_m(const Shape& s) {
+  // Tallest tile the schedule may use; the ragged end of an expert gets shorter tiles (128 / 64 rows) anyway.
   const int mean_rows = s.E > 0 ? s.R / s.E : 0;
-  if (mean_rows >= 1024) return 256;
-  if (mean_rows >= 192) return 128;
+  if (mean_rows >= 256) return 256;
+  if (mean_rows >= 128) return 128;
   return 64;
 }
 
@@ -287,6 +292,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
   g.tile_row0 = ws.tile_row0;
   g.tile_rows = ws.tile_rows;
   g.tile_ready = ws.tile_ready;
+  g.tile_kind = ws.tile_kind;
   g.status = ws.status;
   g.spin_limit = (uint32_t)p->spin_limit;
   g.n_tiles = ws.status + 1;
@@ -311,7 +317,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     a.seg_ready = seg_ready;
     a.ready_epoch = ready_epoch;
     a.n_mfma = p->n_cu;
-    if (launch_layer0(a, p->tile_m, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
+    a.queue_heads = ws.status + 8;
+    if (launch_layer0(a, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
 
   if (!mark(2)) return MOE_ERR_HIP;
@@ -339,7 +346,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.topk_weights = topk_weights;
     b.out = (uint16_t*)out;
     b.combine_counter = ws.status + 4;
-    if (launch_layer1(b, p->tile_m, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
+    b.queue_heads = ws.status + 16;
+    if (launch_layer1(b, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
   if (!mark(3)) return MOE_ERR_HIP;
   if ((p->phases & 8) && !(fused && (p->phases & 4))) {
@@ -393,7 +401,8 @@ int moe_get_index_outputs(const moe_plan_t* p, const void* workspace, int32_t* e
 }
 
 int moe_get_tile_table(const moe_plan_t* p, const void* workspace, int32_t* n_tiles, int32_t* tile_expert,
-                       int32_t* tile_row0, int32_t* tile_rows, int32_t* tile_ready_seg, void* hip_stream) {
+                       int32_t* tile_row0, int32_t* tile_rows, int32_t* tile_ready_seg, int32_t* tile_height,
+                       void* hip_stream) {
   if (!p || !workspace) return MOE_ERR_INVALID_ARG;
   Workspace ws = view(p, const_cast<void*>(workspace));
   hipStream_t st = (hipStream_t)hip_stream;
@@ -404,6 +413,7 @@ int moe_get_tile_table(const moe_plan_t* p, const void* workspace, int32_t* n_ti
   if (!cp(n_tiles, ws.status + 1, 4) || !cp(tile_expert, ws.tile_expert, tb) || !cp(tile_row0, ws.tile_row0, tb) ||
       !cp(tile_rows, ws.tile_rows, tb) || !cp(tile_ready_seg, ws.tile_ready, tb))
     return MOE_ERR_HIP;
+  if (tile_height && launch_tile_heights(ws.tile_kind, tile_height, p->max_tiles, st) != hipSuccess) return MOE_ERR_HIP;
   return MOE_OK;
 }
 

@@ -14,15 +14,17 @@ constexpr int kIndexChunk = 1024;   // (token, slot) pairs handled by one workgr
 constexpr int kTileN = 256;         // columns of B staged per GroupGEMM tile
 constexpr int kTileK = 32;          // depth of one LDS stage
 constexpr int kStages = 4;          // LDS stages in flight
-constexpr int kCombineChunk = 32;   // tokens per unit of combine work
+constexpr int kCombineChunk = 64;   // tokens per unit of combine work
+constexpr int kXcds = 8;            // XCDs of the device: workgroup i runs on XCD i % 8
 
 // Item of a GroupGEMM schedule: M-tile index in the high 20 bits, N-tile index in the low 12.
 __host__ __device__ inline uint32_t pack_item(uint32_t m_tile, uint32_t n_tile) { return (m_tile << 12) | n_tile; }
 
 // Device-side view of the workspace (all pointers into the caller's workspace buffer).
 struct Workspace {
-  int32_t* status;        // [16]  0: device status word, 1: n_tiles, 2: n_items layer0, 3: n_items layer1,
-                          //       4: combine unit counter, 5: layer0 queue counter, 6: layer1 queue counter
+  int32_t* status;        // [64]  0: device status word, 1: n_tiles, 2: n_items layer0, 3: n_items layer1,
+                          //       4: combine unit counter, 8..15: layer0 queue heads (one per XCD),
+                          //       16..23: layer1 queue heads
   int32_t* counts;        // [E]
   int32_t* offsets;       // [E+1]
   int32_t* perm;          // [R] sorted row -> pair id
@@ -33,6 +35,8 @@ struct Workspace {
   int32_t* tile_row0;     // [max_tiles]
   int32_t* tile_rows;     // [max_tiles]
   int32_t* tile_ready;    // [max_tiles] source segment the tile waits for
+  int32_t* tile_kind;     // [max_tiles] 0 / 1 / 2: the tile is computed by the 64 / 128 / 256-row kernel variant
+  int32_t* tile_order;    // [max_tiles] scratch of the schedule builder: tiles sorted tallest first
   uint32_t* items0;       // [max_tiles * n_tiles_n0] layer0 schedule
   uint32_t* items1;       // [max_tiles * n_tiles_n1] layer1 schedule
   uint32_t* panel_done;   // [n_tiles_n1] finished M-tiles per column panel of layer1
@@ -71,12 +75,14 @@ struct GemmParams {
   const int32_t* tile_row0;
   const int32_t* tile_rows;
   const int32_t* tile_ready;
+  const int32_t* tile_kind;
   const uint32_t* items;
   const int32_t* n_items;   // device scalar
   const uint32_t* seg_ready;
   uint32_t ready_epoch;
   uint32_t spin_limit;
   int32_t* status;
+  int32_t* queue_heads;     // [8] next position of each XCD's share of the schedule
   // layer1 only
   uint32_t* panel_done;
   const int32_t* n_tiles;   // device scalar: M-tiles in total
@@ -101,8 +107,9 @@ struct CombineParams {
 // kernel launchers (defined in the .hip files)
 hipError_t launch_route_topk(const float* logits, int T, int E, int k, int32_t* ids, float* w, hipStream_t st);
 hipError_t launch_index_build(const IndexParams& p, hipStream_t st);
-hipError_t launch_layer0(const GemmParams& p, int tile_m, int act, int grid, hipStream_t st);
-hipError_t launch_layer1(const GemmParams& p, int tile_m, int grid, hipStream_t st);
+hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st);
+hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+hipError_t launch_tile_heights(const int32_t* kind, int32_t* height, int n, hipStream_t st);
 
 }  // namespace moe

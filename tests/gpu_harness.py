@@ -63,15 +63,15 @@ class GpuLayer:
         inv = torch.zeros(max(cfg.R, 1), **i32)
         mt = max(moe.moe_plan_max_tiles(self.plan), 1)
         n_tiles = torch.zeros(1, **i32)
-        te, tr0, tr, ts = (torch.zeros(mt, **i32) for _ in range(4))
+        te, tr0, tr, ts, th = (torch.zeros(mt, **i32) for _ in range(5))
         if cfg.T > 0:
             moe.moe_get_index_outputs(self.plan, self.ws, counts, offsets, perm, inv)
-            moe.moe_get_tile_table(self.plan, self.ws, n_tiles, te, tr0, tr, ts)
+            moe.moe_get_tile_table(self.plan, self.ws, n_tiles, te, tr0, tr, ts, th)
         status = moe.moe_last_device_status(self.plan, self.ws) if cfg.T > 0 else 0
         torch.cuda.synchronize()
         n = int(n_tiles.item())
         tiles = {"expert": te[:n].cpu().numpy(), "row0": tr0[:n].cpu().numpy(), "rows": tr[:n].cpu().numpy(),
-                 "ready_seg": ts[:n].cpu().numpy()}
+                 "ready_seg": ts[:n].cpu().numpy(), "height": th[:n].cpu().numpy()}
         return GpuRun(bf16_to_np(self.out), counts.cpu().numpy(), offsets.cpu().numpy(), perm[:cfg.R].cpu().numpy(),
                       inv[:cfg.R].cpu().numpy(), tiles, status)
 

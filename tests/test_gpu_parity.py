@@ -37,11 +37,12 @@ def _check_index(run, cfg, ids, seg_offsets, tile_m):
     np.testing.assert_array_equal(run.offsets, offsets)
     np.testing.assert_array_equal(run.perm, perm)
     np.testing.assert_array_equal(run.inv_perm, inv)
-    ex, r0, nr, rs = orc.layer0_tiles(offsets, perm, cfg.k, seg_offsets, tile_m)
+    ex, r0, nr, rs, ht = orc.layer0_tiles(offsets, perm, cfg.k, seg_offsets, tile_m)
     np.testing.assert_array_equal(run.tiles["expert"], ex)
     np.testing.assert_array_equal(run.tiles["row0"], r0)
     np.testing.assert_array_equal(run.tiles["rows"], nr)
     np.testing.assert_array_equal(run.tiles["ready_seg"], rs)
+    np.testing.assert_array_equal(run.tiles["height"], ht)
 
 
 @pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
@@ -87,7 +88,8 @@ def test_index_outputs_full_size(H, name):
     layer = H.GpuLayer(cfg, inp, ids, w, {"phases": 1})
     layer.forward()
     run = layer.results()
-    tile_m = 256 if cfg.R // cfg.E >= 1024 else 128
+    import paper_2502_19811_amd as moe
+    tile_m = moe.moe_plan_get_option(layer.plan, "tile_m")
     layer.close()
     assert run.status == 0
     _check_index(run, cfg, ids, inp.seg_offsets, tile_m)

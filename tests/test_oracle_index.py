@@ -116,16 +116,17 @@ def test_table3_buffer_sizes():
 
 
 # ---------------------------------------------------------------- tile readiness
-@pytest.mark.parametrize("tile_m", [16, 64, 256])
+@pytest.mark.parametrize("tile_m", [64, 128, 256])
 def test_layer0_tiles_cover_rows_and_ready_segment(tile_m):
     cfg = wl.scaled(wl.CONFIGS["skewed"], T=700, E=8, k=2)
     seg = wl.segment_offsets(cfg)
     ids = _rand_ids(cfg.T, cfg.E, cfg.k, 9)
     _, offsets, perm, _ = orc.build_permutation(ids, cfg.E)
-    ex, r0, nr, rs = orc.layer0_tiles(offsets, perm, cfg.k, seg, tile_m)
+    ex, r0, nr, rs, ht = orc.layer0_tiles(offsets, perm, cfg.k, seg, tile_m)
     covered = np.zeros(cfg.R, np.int32)
-    for e, a, n, s in zip(ex, r0, nr, rs):
-        assert 0 < n <= tile_m and offsets[e] <= a and a + n <= offsets[e + 1]
+    for e, a, n, s, h in zip(ex, r0, nr, rs, ht):
+        assert 0 < n <= h <= tile_m and h in (64, 128, 256) and offsets[e] <= a and a + n <= offsets[e + 1]
+        assert n == h or a + n == offsets[e + 1]                          # only the last tile of an expert is ragged
         covered[a:a + n] += 1
         # brute force: the tile needs every row's source segment, i.e. the latest of them
         toks = perm[a:a + n] // cfg.k
@@ -133,7 +134,10 @@ def test_layer0_tiles_cover_rows_and_ready_segment(tile_m):
         assert s == max(segs)
         assert segs == sorted(segs)                                      # rows inside a tile are in source order
     assert (covered == 1).all()
-    assert len(ex) == sum(-(-int(c) // tile_m) for c in np.diff(offsets))
+    # padding: never more than 63 rows per expert unless the remainder needs the full-height tile
+    for e in range(cfg.E):
+        pad = int(ht[ex == e].sum()) - int(offsets[e + 1] - offsets[e])
+        assert 0 <= pad < 64
 
 
 def test_segment_offsets_properties():
