@@ -1,0 +1,95 @@
+"""Host-side behaviour of the C ABI (no GPU needed): the library loads, exports what the header declares, validates
+arguments and sizes workspaces."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2502_19811_amd as moe
+from paper_2502_19811_amd import binding
+from conftest import ROOT, read_golden
+
+SEG8 = [0, 16, 32, 48, 64, 80, 96, 112, 128]
+
+
+def test_library_exports_every_declared_symbol():
+    lib = moe.load_library()
+    header = open(os.path.join(ROOT, "include", "moe_gfx950.h")).read()
+    declared = set(re.findall(r"^(?:int|size_t|int32_t|const char \*)\s*(moe_[a-z0-9_]+)\(", header, flags=re.M))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+    assert declared == set(binding.EXPORTS)
+
+
+def test_status_strings():
+    assert moe.moe_status_string(0) == "ok"
+    for code in range(-6, 0):
+        assert moe.moe_status_string(code) not in ("ok", "unknown status")
+    assert moe.moe_status_string(-99) == "unknown status"
+
+
+def _create(**kw):
+    a = dict(T=128, H=256, F=512, E=4, k=2, S=8, act=moe.MOE_ACT_GELU, seg_offsets=SEG8)
+    a.update(kw)
+    return moe.moe_plan_create(**a)
+
+
+def test_plan_create_and_options():
+    plan = _create()
+    assert moe.moe_plan_workspace_bytes(plan) > 256 * (512 + 256) * 2           # holds h [R,F] and Y [R,H], R = 256
+    assert moe.moe_plan_get_option(plan, "tile_m") in (64, 128, 256)
+    for key, val in [("tile_m", 128), ("n_dm", 7), ("layer0_order", 1), ("layer1_order", 0), ("spin_limit", 1000),
+                     ("phases", 3), ("n_cu", 64)]:
+        moe.moe_plan_set_option(plan, key, val)
+        assert moe.moe_plan_get_option(plan, key) == val
+    for key, val in [("tile_m", 100), ("n_dm", -2), ("layer0_order", 2), ("phases", 16), ("no_such_key", 1)]:
+        with pytest.raises(moe.MoEError) as e:
+            moe.moe_plan_set_option(plan, key, val)
+        assert e.value.status == -1
+    assert moe.moe_plan_max_tiles(plan) >= 256 // 128 + 4
+    moe.moe_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(H=0), -1), (dict(k=5), -1), (dict(act=7), -1), (dict(seg_offsets=[0, 16, 32, 48, 64, 80, 96, 112, 127]), -1),
+    (dict(seg_offsets=[0, 32, 16, 48, 64, 80, 96, 112, 128]), -1),
+    (dict(H=200), -4), (dict(F=300), -4), (dict(E=300, k=2), -4), (dict(S=65, seg_offsets=[0] * 65 + [128]), -4),
+    (dict(act=moe.MOE_ACT_SWIGLU, F=192), -4),
+])
+def test_plan_create_rejects(kw, status):
+    with pytest.raises(moe.MoEError) as e:
+        _create(**kw)
+    assert e.value.status == status
+
+
+def test_forward_argument_checks_happen_before_any_gpu_work():
+    lib = moe.load_library()
+    plan = _create()
+    need = moe.moe_plan_workspace_bytes(plan)
+    buf = C.create_string_buffer(4096)
+    addr = (C.addressof(buf) + 255) & ~255           # a 256-byte aligned non-NULL pointer; never dereferenced
+    args = [plan, addr, addr, addr, addr, addr, moe.MOE_ACT_GELU, addr, addr, need, None, 0, None]
+    bad = list(args); bad[1] = None
+    assert lib.moe_layer_forward(*bad) == -1          # NULL x
+    bad = list(args); bad[6] = moe.MOE_ACT_SWIGLU
+    assert lib.moe_layer_forward(*bad) == -2          # act differs from the plan
+    bad = list(args); bad[9] = need - 1
+    assert lib.moe_layer_forward(*bad) == -3          # workspace too small
+    bad = list(args); bad[1] = addr + 2
+    assert lib.moe_layer_forward(*bad) == -1          # misaligned x
+    bad = list(args); bad[8] = addr + 16
+    assert lib.moe_layer_forward(*bad) == -1          # workspace not 256-byte aligned
+    moe.moe_plan_destroy(plan)
+
+
+def test_receive_buffer_bytes_table3():
+    for M, N, mb in [[int(v) for v in r] for r in read_golden("table3_buffer_mb.txt")]:
+        assert moe.moe_receive_buffer_bytes(M, N) == mb << 20
+
+
+def test_empty_batch_plan():
+    plan = _create(T=0, seg_offsets=[0] * 9)
+    assert moe.moe_plan_workspace_bytes(plan) > 0
+    moe.moe_plan_destroy(plan)

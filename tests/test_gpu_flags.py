@@ -1,0 +1,112 @@
+"""Ready flags, schedule orders and failure handling of the HIP path (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import moe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _cfg():
+    return wl.MoEConfig("flags", T=1024, H=512, F=768, E=8, k=2, act=wl.ACT_SWIGLU, S=8, seed=300)
+
+
+def _setup(options=None, cfg=None):
+    import gpu_harness as H
+    cfg = cfg or _cfg()
+    inp = wl.make_inputs(cfg, threads=4)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    return H, cfg, inp, ids, w, H.GpuLayer(cfg, inp, ids, w, options or {})
+
+
+def test_output_is_deterministic_and_independent_of_the_schedule():
+    H, cfg, inp, ids, w, layer = _setup()
+    layer.forward(); base = layer.results(); layer.close()
+    ref = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    a, b = H.error_metrics(base.out, ref)
+    assert a <= H.REL_TOL and b <= H.REL_TOL
+    for opts in ({}, {"layer0_order": 1}, {"layer1_order": 0}, {"n_dm": 16}, {"tile_m": 128}, {"n_cu": 64}):
+        print(f"options {opts}", flush=True)
+        _, _, _, _, _, l2 = _setup(opts)
+        l2.forward(); r2 = l2.results(); l2.close()
+        assert r2.status == 0
+        # every output element is the same sum in the same order whatever the tiling and schedule
+        np.testing.assert_array_equal(r2.out, base.out)
+        np.testing.assert_array_equal(r2.perm, base.perm)
+
+
+def test_segment_boundaries_do_not_change_the_result():
+    H, cfg, inp, ids, w, layer = _setup()
+    layer.forward(); base = layer.results(); layer.close()
+    other = wl.scaled(cfg, S=3)
+    inp2 = wl.MoEInputs(other, inp.x, inp.W1, inp.W2, inp.logits, np.array([0, 100, 100, 1024], np.int32))
+    l2 = H.GpuLayer(other, inp2, ids, w)
+    l2.forward(); r2 = l2.results(); l2.close()
+    np.testing.assert_array_equal(r2.out, base.out)
+    np.testing.assert_array_equal(r2.perm, base.perm)
+    assert set(r2.tiles["ready_seg"].tolist()) <= {0, 2}      # the empty segment 1 owns no row
+
+
+def test_flags_arriving_late_and_out_of_order():
+    # 64 of the compute units stay free for the flag writes of the side stream; the spin limit turns a lost flag into
+    # an error instead of a hang
+    H, cfg, inp, ids, w, layer = _setup({"n_cu": 128, "spin_limit": 1 << 24})
+    layer.forward(); base = layer.results()
+    flags = torch.zeros(cfg.S, dtype=torch.int32, device="cuda")
+    host_vals = torch.full((cfg.S,), 7, dtype=torch.int32).pin_memory()
+    torch.cuda.synchronize()
+    layer.out.zero_()
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    print("forward waiting on flags", flush=True)
+    layer.forward(seg_ready=flags, epoch=7, stream=main)
+    with torch.cuda.stream(side):
+        for s in [3, 0, 7, 1, 6, 2, 5, 4]:
+            torch.cuda._sleep(2_000_000)                     # roughly a millisecond between arrivals
+            flags[s:s + 1].copy_(host_vals[s:s + 1], non_blocking=True)
+    side.synchronize()
+    run = layer.results()
+    layer.close()
+    assert run.status == 0
+    np.testing.assert_array_equal(run.out, base.out)
+
+
+def test_missing_flag_times_out_instead_of_hanging():
+    H, cfg, inp, ids, w, layer = _setup({"n_cu": 128, "spin_limit": 2000})
+    flags = torch.full((cfg.S,), 5, dtype=torch.int32, device="cuda")
+    flags[cfg.S - 1] = 4                                      # the last segment never reaches epoch 5
+    print("forward with a flag that never arrives", flush=True)
+    layer.forward(seg_ready=flags, epoch=5)
+    run = layer.results()
+    assert run.status == -6                                   # MOE_ERR_TIMEOUT, reported by the kernels
+    # the same plan and workspace work again once the flag is there
+    flags[cfg.S - 1] = 5
+    layer.forward(seg_ready=flags, epoch=5)
+    run2 = layer.results()
+    layer.close()
+    assert run2.status == 0
+    ref = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    a, b = H.error_metrics(run2.out, ref)
+    assert a <= H.REL_TOL and b <= H.REL_TOL
+
+
+def test_empty_batch_and_empty_experts():
+    import gpu_harness as H
+    import paper_2502_19811_amd as moe
+    plan = moe.moe_plan_create(0, 256, 256, 4, 2, 2, moe.MOE_ACT_GELU, [0, 0, 0])
+    z = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(max(256, moe.moe_plan_workspace_bytes(plan)), dtype=torch.uint8, device="cuda")
+    moe.moe_layer_forward(plan, z, z, z, z, z, moe.MOE_ACT_GELU, z, ws)      # T = 0: nothing to do, no error
+    moe.moe_plan_destroy(plan)
+    # all tokens to experts 1 and 2 of 6: four experts receive no row at all
+    cfg = wl.MoEConfig("hole", T=90, H=256, F=256, E=6, k=2, act=wl.ACT_GELU, S=2, seed=301)
+    inp = wl.make_inputs(cfg, threads=2)
+    ids = np.tile(np.array([[1, 2]], np.int32), (cfg.T, 1))
+    w = np.tile(np.array([[0.75, 0.25]], np.float32), (cfg.T, 1))
+    layer = H.GpuLayer(cfg, inp, ids, w)
+    layer.forward(); run = layer.results(); layer.close()
+    assert run.counts.tolist() == [0, 90, 90, 0, 0, 0]
+    a, b = H.error_metrics(run.out, orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act))
+    assert a <= H.REL_TOL and b <= H.REL_TOL
