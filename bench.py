@@ -31,6 +31,8 @@ def main() -> int:
     ap.add_argument("--opt", action="append", default=[], help="plan option key=value (repeatable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures the one-GPU share of the layer; --gpus above 1 is not part of this build "
@@ -70,6 +72,12 @@ def main() -> int:
     def step():
         moe.moe_layer_forward(plan, x, ids, w, W1, W2, cfg.act, out, ws, None, 0, stream)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -92,11 +100,14 @@ def main() -> int:
     l1_flop = 2.0 * cfg.R * cfg.F * cfg.H
     l0_tflops = l0_flop / (phase_ms[1] * 1e-3) / 1e12 if phase_ms[1] > 0 else 0.0
     l1_tflops = l1_flop / (phase_ms[2] * 1e-3) / 1e12 if phase_ms[2] > 0 else 0.0
+    # HBM-side bytes per launch of that kernel, from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+    # each scaled by what the counter reads for a plain 1 GiB copy); None if no summary exists for this workload
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"layer0_gemm_{cfg.name}_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", f"group_gemm_{cfg.name}_pmc_traffic.md")
     if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+        for line in open(tpath):
+            if line.startswith("hbm_bytes_per_launch layer0:"):
+                traffic = float(line.split(":")[1])
 
     result = {
         "metric": METRIC,

@@ -65,8 +65,9 @@ int moe_plan_destroy(moe_plan_t *plan);
 /* Tunables.  Keys:
  *   "tile_m"       64 / 128 / 256: rows of the tallest GroupGEMM tile (default: chosen from T*k/E)
  *   "n_dm"         data-movement workgroups of the layer1 kernel (default: table lookup per shape)
- *   "layer1_order" 0 = expert-major tiles, separate combine kernel afterwards;
- *                  1 = column-panel-major tiles (Fig. 6), combine workgroups inside the GEMM kernel
+ *   "layer1_order" 1 = finished column panels (Fig. 6) are reduced inside the layer1 kernel, by its n_dm
+ *                  data-movement workgroups and by GEMM workgroups that ran out of tiles (default);
+ *                  0 = a separate combine kernel after the layer1 kernel
  *   "layer0_order" 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5)
  *   "spin_limit"   >0: a wait on a ready flag gives up after that many polls and the forward
  *                  reports MOE_ERR_TIMEOUT through moe_last_device_status (0 = wait for ever)
