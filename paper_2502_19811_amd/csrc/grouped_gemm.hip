@@ -47,6 +47,14 @@ __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
                : "memory");
 }
+// Tells the compiler that a pointer / integer is the same in every lane (keeps it in scalar registers).
+__device__ __forceinline__ const char* uniform(const char* ptr) {
+  const uint64_t v = (uint64_t)(uintptr_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -200,15 +208,26 @@ __device__ __forceinline__ void combine_loop(const GemmParams& p, int32_t* lds_s
   }
 }
 
-// Next position of XCD x's share of the schedule (positions x, x + 8, x + 16, ...); may lie past the end.
-__device__ __forceinline__ int take_from(const GemmParams& p, int x) {
-  return __hip_atomic_fetch_add(&p.queue_heads[x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * kXcds + x;
+// ---------------------------------------------------------------------------------------------
+// Schedule queues: XCD x owns the list positions base[x] + i * stride, i < len[x].
+// ---------------------------------------------------------------------------------------------
+struct Queue {
+  int own_len, own_base;   // this workgroup's XCD, read once
+};
+__device__ __forceinline__ int queue_pos(const GemmParams& p, int x, int i) {
+  return (p.queue_base ? p.queue_base[x] : x) + i * p.queue_stride;
 }
-// Own share first, then the other XCDs' leftovers; -1 when the schedule is used up.
-__device__ __forceinline__ int take_any(const GemmParams& p, int xcd, int first_offset, int n_items) {
-  for (int d = first_offset; d < kXcds; d++) {
-    const int idx = take_from(p, (xcd + d) & (kXcds - 1));
-    if (idx < n_items) return idx;
+// Takes the next item of XCD x's queue; returns its list position or -1 when that queue is used up.
+__device__ __forceinline__ int take_from(const GemmParams& p, int x, int len, int base) {
+  const int i = __hip_atomic_fetch_add(&p.queue_heads[x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return i < len ? base + i * p.queue_stride : -1;
+}
+// The other XCDs' leftovers, nearest first; -1 when every queue is used up.
+__device__ __forceinline__ int steal(const GemmParams& p, int xcd) {
+  for (int d = 1; d < kXcds; d++) {
+    const int x = (xcd + d) & (kXcds - 1);
+    const int idx = take_from(p, x, p.queue_len[x], queue_pos(p, x, 0));
+    if (idx >= 0) return idx;
   }
   return -1;
 }
@@ -222,11 +241,117 @@ __device__ __forceinline__ void publish_panel(const GemmParams& p, int panel) {
   if (threadIdx.x == 0) __hip_atomic_fetch_add(&p.panel_done[panel], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// One tile of BM = WM*MT*32 rows by 256 columns.  lds_slot[0] receives the schedule position this workgroup
-// works on next (fetched while this tile runs).
+// What a workgroup knows about a tile before it starts on it.
+struct Tile {
+  int idx;        // list position, -1: none
+  ItemRec rec;
+  int arow[4];    // rows of A this lane loads per stage (layer0: gathered token rows, layer1: rows of h)
+};
+__device__ __forceinline__ ItemRec make_uniform(ItemRec r) {
+  r.m_tile = uniform(r.m_tile); r.n_tile = uniform(r.n_tile); r.expert = uniform(r.expert); r.row0 = uniform(r.row0);
+  r.nrows = uniform(r.nrows); r.kind = uniform(r.kind); r.ready_seg = uniform(r.ready_seg);
+  return r;
+}
+__device__ __forceinline__ ItemRec load_item(const GemmParams& p, int idx) { return make_uniform(p.items[idx]); }
+// Global offsets and running base pointers of a tile's operand loads.
+struct LoadState {
+  uint32_t aoff[4], boff[4];
+  const char* Ab;
+  const char* Bb;
+};
+
+constexpr int kStagingOffset = 3 * (256 * BK * 2 + B_STAGE);   // the epilogue stages C in the last 32 KiB of LDS
+
+// Rows of A the lane loads for a tile of the given height class (LA = 1, 2 or 4 loads per stage).
+template <int MODE>
+__device__ __forceinline__ void load_arows(const GemmParams& p, Tile& t, int lane, int w) {
+  const int la = 1 << t.rec.kind;
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    if (j < la) {
+      const int r = (w * la + j) * 16 + (lane >> 2);
+      const int sr = t.rec.row0 + (r < t.rec.nrows ? r : t.rec.nrows - 1);   // past the ragged end: the last row again
+      t.arow[j] = MODE != MODE_L1 ? p.a_rows[sr] : sr;
+    }
+  }
+}
+
+// Address set-up of a tile and the loads of its first NS-1 stages.
 template <int WM, int MT, int NT, int MODE>
-__device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, int m_tile,
-                                         int n_tile, int xcd, int n_items, int& pending_panel) {
+__device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t lds0, const Tile& t, LoadState& ls, int lane,
+                                                int w) {
+  constexpr int BM = WM * MT * 32;
+  constexpr int A_STAGE = BM * BK * 2;
+  constexpr int STAGE = A_STAGE + B_STAGE;
+  constexpr int LA = BM / 64, LB = 4;
+#pragma unroll
+  for (int j = 0; j < LA; j++) {
+    const int r = (w * LA + j) * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((r >> 2) & 3);
+    ls.aoff[j] = (uint32_t)t.arow[j] * p.lda_bytes + c * 16;
+  }
+  const int col0 = (MODE == MODE_L0_SWIGLU) ? t.rec.n_tile * (BN / 2) : t.rec.n_tile * BN;
+#pragma unroll
+  for (int j = 0; j < LB; j++) {
+    const int kr = (w * LB + j) * 2 + (lane >> 5);
+    const int cpb = lane & 31;
+    const int blk = (cpb >> 2) ^ ((kr & 3) | (((kr >> 3) & 1) << 2));
+    const int c8 = (blk * 4 + (cpb & 3)) * 8;  // column of the tile this lane fetches
+    int gcol;
+    if (MODE == MODE_L0_SWIGLU) {
+      // a wavefront's 32*NT columns are [gate | up] of the same 16*NT hidden units
+      const int region = c8 / (NT * 32), within = c8 % (NT * 32);
+      const int half = within / (NT * 16), fo = within % (NT * 16);
+      gcol = half * p.F + col0 + region * (NT * 16) + fo;
+    } else {
+      gcol = col0 + c8;
+    }
+    ls.boff[j] = ((uint32_t)kr * p.ldb + gcol) * 2;
+  }
+  ls.Ab = uniform(p.A);
+  ls.Bb = uniform(p.B + (uint64_t)t.rec.expert * p.b_expert_bytes);
+  const size_t bstep = (size_t)BK * p.ldb * 2;
+#pragma unroll
+  for (int s = 0; s < NS - 1; s++) {
+#pragma unroll
+    for (int j = 0; j < LA; j++) dma16(ls.Ab, ls.aoff[j], lds0 + s * STAGE + (w * LA + j) * 1024);
+#pragma unroll
+    for (int j = 0; j < LB; j++) dma16(ls.Bb, ls.boff[j], lds0 + s * STAGE + A_STAGE + (w * LB + j) * 1024);
+    ls.Ab += BK * 2;
+    ls.Bb += bstep;
+  }
+}
+
+// Workgroup-wide: is the source segment of tile t there?  block = true waits for it (up to the spin limit).
+template <int MODE>
+__device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t, volatile int32_t* lds_slot, bool block) {
+  if (MODE == MODE_L1 || p.seg_ready == nullptr) return true;
+  if (threadIdx.x == 0) {
+    const uint32_t* flag = &p.seg_ready[t.rec.ready_seg];
+    bool ok;
+    if (block) {
+      ok = spin_until_ge(flag, p.ready_epoch, p.spin_limit);
+      if (!ok) atomicExch(p.status, (int)MOE_ERR_TIMEOUT);
+    } else {
+      ok = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) >= p.ready_epoch;
+    }
+    lds_slot[1] = ok;
+  }
+  __syncthreads();
+  const bool ok = lds_slot[1] != 0;
+  __syncthreads();
+  if (ok) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+  return ok;
+}
+
+// One tile of BM = WM*MT*32 rows by 256 columns: address set-up and first loads, main loop, epilogue.  While the
+// tile runs the workgroup finds out what its next tile is without waiting for any of the round trips: the queue
+// atomic is issued up front; once the last operand load has landed (48 MFMAs before the end) its result is shared
+// through LDS and the item record is requested; the rows of A the next tile gathers are requested before the
+// epilogue.  next.idx = -1: no further tile.
+template <int WM, int MT, int NT, int MODE>
+__device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, const Tile& cur,
+                                         Tile& next, int xcd, const Queue& q, int& pending_panel) {
   constexpr int WN = 4 / WM;
   constexpr int BM = WM * MT * 32;
   static_assert(WN * NT * 32 == BN, "tile must be 256 columns wide");
@@ -245,6 +370,8 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = w / WN, wn = w % WN;
   const int g = lane >> 4, j16 = lane & 15;
+  const int row0 = uniform(cur.rec.row0), nrows = uniform(cur.rec.nrows), n_tile = uniform(cur.rec.n_tile);
+  const int col0 = (MODE == MODE_L0_SWIGLU) ? n_tile * (BN / 2) : n_tile * BN;
 
   // LDS read addresses (stage 0)
   uint32_t a_rd[2], b_rd[NT];
@@ -259,121 +386,83 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     for (int nt = 0; nt < NT; nt++)
       b_rd[nt] = lds0 + A_STAGE + krow * 512 + (((wn * NT + nt) ^ swz) << 6) + (16 * (g & 1) + 4 * (j16 & 3)) * 2;
   }
-  {
-    const int expert = p.tile_expert[m_tile];
-    const int row0 = p.tile_row0[m_tile];
-    const int nrows = p.tile_rows[m_tile];
+  // address set-up and the loads of the first NS-1 stages
+  LoadState ls;
+  setup_and_issue<WM, MT, NT, MODE>(p, lds0, cur, ls, lane, w);
+  const char* Ab = uniform(ls.Ab);
+  const char* Bb = uniform(ls.Bb);
+  const size_t bstep = (size_t)BK * p.ldb * 2;
 
-    // per-lane global offsets of the loads of one stage
-    uint32_t aoff[LA], boff[LB];
+  f32x16 acc[MT][NT];
 #pragma unroll
-    for (int j = 0; j < LA; j++) {
-      const int r = (w * LA + j) * 16 + (lane >> 2);
-      const int c = (lane & 3) ^ ((r >> 2) & 3);
-      int sr = row0 + (r < nrows ? r : nrows - 1);   // rows past the ragged end re-read the last row
-      if (MODE != MODE_L1) sr = p.a_rows[sr];
-      aoff[j] = (uint32_t)sr * p.lda_bytes + c * 16;
+  for (int i = 0; i < MT; i++)
+#pragma unroll
+    for (int j = 0; j < NT; j++) acc[i][j] = (f32x16){0};
+
+  // One stage = LA loads of A rows and LB loads of B rows per lane.  The loads are issued one at a time between
+  // groups of MFMAs: a burst would fill the vector-memory queue and stall the MFMAs queued behind it.
+  auto issue_a = [&](int stage, int j) { dma16(Ab, ls.aoff[j], lds0 + stage * STAGE + (w * LA + j) * 1024); };
+  auto issue_b = [&](int stage, int j) { dma16(Bb, ls.boff[j], lds0 + stage * STAGE + A_STAGE + (w * LB + j) * 1024); };
+  auto advance = [&]() {
+    Ab += BK * 2;
+    Bb += bstep;
+  };
+  bf16x8 af[2][MT], bfr[2][NT];
+  // Group q (of 4) of a half step: the LDS reads of fragment q for the next half step and a quarter of the MFMAs
+  // of this one.  rd_off / rd_kk: stage offset and 16-deep sub-step the fragments are read from.
+  auto group = [&](int cb, int nb, uint32_t rd_off, int rd_kk, int q) {
+    constexpr int PER = MT * NT / 4;
+    if (q < MT) af[nb][q] = lds_read_a(rd_off + a_rd[rd_kk] + q * 32 * 64);
+    if (q < NT)
+      bfr[nb][q] = lds_read_b(rd_off + b_rd[q] + rd_kk * 16 * 512, rd_off + b_rd[q] + (rd_kk * 16 + 4) * 512);
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      const int m = q * PER + i, mt = m / NT, nt = m % NT;
+      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][nt], af[cb][mt], acc[mt][nt], 0, 0, 0);
     }
-    const int col0 = (MODE == MODE_L0_SWIGLU) ? n_tile * (BN / 2) : n_tile * BN;
+    const int n_reads = (q < MT ? 1 : 0) + (q < NT ? 2 : 0);
 #pragma unroll
-    for (int j = 0; j < LB; j++) {
-      const int kr = (w * LB + j) * 2 + (lane >> 5);
-      const int cpb = lane & 31;
-      const int blk = (cpb >> 2) ^ ((kr & 3) | (((kr >> 3) & 1) << 2));
-      const int c8 = (blk * 4 + (cpb & 3)) * 8;  // column of the tile this lane fetches
-      int gcol;
-      if (MODE == MODE_L0_SWIGLU) {
-        // a wavefront's 32*NT columns are [gate | up] of the same 16*NT hidden units
-        const int region = c8 / (NT * 32), within = c8 % (NT * 32);
-        const int half = within / (NT * 16), fo = within % (NT * 16);
-        gcol = half * p.F + col0 + region * (NT * 16) + fo;
-      } else {
-        gcol = col0 + c8;
-      }
-      boff[j] = ((uint32_t)kr * p.ldb + gcol) * 2;
+    for (int i = 0; i < PER; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    const char* Ab = p.A;
-    const char* Bb = p.B + (uint64_t)expert * p.b_expert_bytes;
-    const size_t bstep = (size_t)BK * p.ldb * 2;
-
-    f32x16 acc[MT][NT];
 #pragma unroll
-    for (int i = 0; i < MT; i++)
+    for (int i = PER; i < 3; i++)
+      if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  };
+  auto half1 = [&](int stage_issue, bool do_issue, uint32_t so) {
 #pragma unroll
-      for (int j = 0; j < NT; j++) acc[i][j] = (f32x16){0};
-
-    // One stage = LA loads of A rows and LB loads of B rows per lane.  The loads are issued one at a time between
-    // groups of MFMAs: a burst would fill the vector-memory queue and stall the MFMAs queued behind it.
-    auto issue_a = [&](int stage, int j) { dma16(Ab, aoff[j], lds0 + stage * STAGE + (w * LA + j) * 1024); };
-    auto issue_b = [&](int stage, int j) { dma16(Bb, boff[j], lds0 + stage * STAGE + A_STAGE + (w * LB + j) * 1024); };
-    auto advance = [&]() {
-      Ab += BK * 2;
-      Bb += bstep;
-    };
-    bf16x8 af[2][MT], bfr[2][NT];
-    // Group q (of 4) of a half step: the LDS reads of fragment q for the next half step and a quarter of the MFMAs
-    // of this one.  rd_off / rd_kk: stage offset and 16-deep sub-step the fragments are read from.
-    auto group = [&](int cur, int nxt, uint32_t rd_off, int rd_kk, int q) {
-      constexpr int PER = MT * NT / 4;
-      if (q < MT) af[nxt][q] = lds_read_a(rd_off + a_rd[rd_kk] + q * 32 * 64);
-      if (q < NT)
-        bfr[nxt][q] = lds_read_b(rd_off + b_rd[q] + rd_kk * 16 * 512, rd_off + b_rd[q] + (rd_kk * 16 + 4) * 512);
-#pragma unroll
-      for (int i = 0; i < PER; i++) {
-        const int m = q * PER + i, mt = m / NT, nt = m % NT;
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][nt], af[cur][mt], acc[mt][nt], 0, 0, 0);
-      }
-      const int n_reads = (q < MT ? 1 : 0) + (q < NT ? 2 : 0);
-#pragma unroll
-      for (int i = 0; i < PER; i++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-#pragma unroll
-      for (int i = PER; i < 3; i++)
-        if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    };
-    auto half1 = [&](int stage_issue, bool do_issue, uint32_t so) {
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        if (do_issue && q < LA) issue_a(stage_issue, q);
-        group(0, 1, so, 1, q);
-      }
-    };
-    auto half2 = [&](int stage_issue, bool do_issue, uint32_t sn) {
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        if (do_issue && q < LB) issue_b(stage_issue, q);
-        group(1, 0, sn, 0, q);
-      }
-    };
-
-    // The next schedule position is requested after the row indices have been read and before this tile's loads are
-    // issued: the atomic is then the oldest outstanding memory operation of the wavefront, so it neither delays the
-    // address set-up nor disturbs the load counts waited for below.
-    asm volatile("" ::: "memory");
-    int next_idx = 0;
-    if (tid == 0) next_idx = take_from(p, xcd);
-    asm volatile("" ::: "memory");
-
-    const int nk = p.K / BK;  // >= NS - 1 (checked on the host)
-#pragma unroll
-    for (int s = 0; s < NS - 1; s++) {
-#pragma unroll
-      for (int j = 0; j < LA; j++) issue_a(s, j);
-#pragma unroll
-      for (int j = 0; j < LB; j++) issue_b(s, j);
-      advance();
+    for (int q = 0; q < 4; q++) {
+      if (do_issue && q < LA) issue_a(stage_issue, q);
+      group(0, 1, so, 1, q);
     }
-    wait_vmcnt<(NS - 2) * LS>();
-    block_barrier();
+  };
+  auto half2 = [&](int stage_issue, bool do_issue, uint32_t sn) {
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(a_rd[0] + mt * 32 * 64);
-#pragma unroll
-    for (int nt = 0; nt < NT; nt++) bfr[0][nt] = lds_read_b(b_rd[nt], b_rd[nt] + 4 * 512);
+    for (int q = 0; q < 4; q++) {
+      if (do_issue && q < LB) issue_b(stage_issue, q);
+      group(1, 0, sn, 0, q);
+    }
+  };
 
-    int kt = 0;
-    for (; kt < nk - (NS - 1); kt++) {
+  // The next item of this XCD's queue is requested before anything else of this tile is outstanding; the
+  // operand loads of the first stages were issued before (by the previous tile, or by the kernel for the first).
+  int next_raw = 0;
+  if (tid == 0) next_raw = take_from(p, xcd, q.own_len, q.own_base);
+
+  const int nk = p.K / BK;  // >= NS - 1 (checked on the host)
+  // first stage landed?  Everything issued after it (two more stages, and whatever the previous tile's epilogue
+  // stored) may still be outstanding; loads return in order, so at most 2*LS outstanding means stage 0 is there.
+  wait_vmcnt<(NS - 2) * LS>();
+  block_barrier();
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(a_rd[0] + mt * 32 * 64);
+#pragma unroll
+  for (int nt = 0; nt < NT; nt++) bfr[0][nt] = lds_read_b(b_rd[nt], b_rd[nt] + 4 * 512);
+
+  int kt = 0;
+  auto steady = [&](int kt_end) {
+    for (; kt < kt_end; kt++) {
       const int st = (kt + NS - 1) % NS;
       half1(st, true, (kt % NS) * STAGE);
       // stage kt+1 has landed for this lane (younger: stage kt+2 and the A rows of stage kt+3); after the barrier
@@ -383,89 +472,101 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       half2(st, true, ((kt + 1) % NS) * STAGE);
       advance();
     }
-    half1(0, false, (kt % NS) * STAGE);
-    wait_vmcnt<LS>();
-    block_barrier();
-    half2(0, false, ((kt + 1) % NS) * STAGE);
-    kt++;
-    half1(0, false, (kt % NS) * STAGE);
-    wait_vmcnt<0>();
-    block_barrier();
-    half2(0, false, ((kt + 1) % NS) * STAGE);
-    kt++;
-    half1(0, false, (kt % NS) * STAGE);
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-      for (int nt = 0; nt < NT; nt++)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[1][nt], af[1][mt], acc[mt][nt], 0, 0, 0);
+  };
+  steady(nk - (NS - 1));
 
-    // hand the next schedule position to the whole workgroup (read after the barrier at the top of the tile loop)
-    if (tid == 0) {
-      if (next_idx >= n_items) next_idx = take_any(p, xcd, 1, n_items);
-      lds_slot[0] = next_idx;
-    }
+  half1(0, false, (kt % NS) * STAGE);
+  wait_vmcnt<LS>();
+  block_barrier();
+  half2(0, false, ((kt + 1) % NS) * STAGE);
+  kt++;
+  half1(0, false, (kt % NS) * STAGE);
+  wait_vmcnt<0>();
+  // No operand load is in flight any more, so memory operations the compiler waits for by itself no longer stall
+  // behind them: thread 0 turns its queue ticket into a list position (stealing from other XCDs if its own queue is
+  // used up) and hands it to the workgroup across the barrier; everybody then asks for the item record, whose
+  // latency the remaining 48 MFMAs cover.
+  if (tid == 0) {
+    if (next_raw < 0) next_raw = steal(p, xcd);
+    lds_slot[0] = next_raw;
+  }
+  block_barrier();
+  next.idx = uniform((int)lds_slot[0]);
+  ItemRec raw_rec;
+  if (next.idx >= 0) raw_rec = p.items[next.idx];
+  half2(0, false, ((kt + 1) % NS) * STAGE);
+  kt++;
+  half1(0, false, (kt % NS) * STAGE);
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++)
+      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[1][nt], af[1][mt], acc[mt][nt], 0, 0, 0);
 
-    // Epilogue.  The MFMAs ran with the operands swapped (B fragment first), so a lane holds, for output row
-    // lane & 31 of each 32x32 block, the columns 8*(i/4) + 4*(lane/32) + i%4: four consecutive columns per group of
-    // four accumulator registers.  The wavefront's part of the tile is staged in LDS as bf16 (8-byte writes, 16-byte
-    // chunks XOR-swizzled by row) and written out in full 16-byte pieces, whole rows at a time; 2-byte stores straight
-    // from the accumulators cost a tenth of the tile's time.
-    constexpr int OUT_NT = (MODE == MODE_L0_SWIGLU) ? NT / 2 : NT;   // 32-column blocks of output per wavefront
-    constexpr int RB = OUT_NT * 64;                                   // bytes per staged row
-    constexpr int NC = RB / 16;                                       // 16-byte chunks per staged row
-    constexpr int RPB = RB >= 256 ? 1 : 256 / RB;                     // rows per 256 bytes of LDS banks
-    // The previous tile is published only now: its stores have drained during this tile's main loop, so the release
-    // does not wait for them (publishing right after the stores would stall the next tile behind the store burst).
-    if (MODE == MODE_L1 && pending_panel >= 0) {
-      publish_panel(p, pending_panel);
-      pending_panel = -1;
-    }
-    block_barrier();   // every wavefront is done reading the operand stages
-    const uint32_t cbase = lds0 + w * (MT * 32 * RB);
-    int lane_e = lane;   // opaque again: the epilogue's addresses are computed here, not before the main loop
-    asm volatile("" : "+v"(lane_e));
+  // The previous tile is published only now: its stores have drained during this tile's main loop, so the release
+  // does not wait for them (publishing right after the stores would stall the next tile behind the store burst).
+  if (MODE == MODE_L1 && pending_panel >= 0) {
+    publish_panel(p, pending_panel);
+    pending_panel = -1;
+  }
+  block_barrier();   // every wavefront is done reading the operand stages
+
+  if (next.idx >= 0) next.rec = make_uniform(raw_rec);
+
+  // Epilogue.  The MFMAs ran with the operands swapped (B fragment first), so a lane holds, for output row
+  // lane & 31 of each 32x32 block, the columns 8*(i/4) + 4*(lane/32) + i%4: four consecutive columns per group of
+  // four accumulator registers.  One 32-row block at a time, the wavefront's part of the tile is staged in LDS as
+  // bf16 (8-byte writes, 16-byte chunks XOR-swizzled by row) and written out in full 16-byte pieces, whole rows at
+  // a time; 2-byte stores straight from the accumulators cost a tenth of the tile's time.
+  constexpr int OUT_NT = (MODE == MODE_L0_SWIGLU) ? NT / 2 : NT;   // 32-column blocks of output per wavefront
+  constexpr int RB = OUT_NT * 64;                                   // bytes per staged row
+  constexpr int NC = RB / 16;                                       // 16-byte chunks per staged row
+  constexpr int RPB = RB >= 256 ? 1 : 256 / RB;                     // rows per 256 bytes of LDS banks
+  const uint32_t cbase = lds0 + kStagingOffset + w * (32 * RB);     // 32 rows x RB bytes per wavefront (<= 8 KiB)
+  int lane_e = lane;   // opaque again: the epilogue's addresses are computed here, not before the main loop
+  asm volatile("" : "+v"(lane_e));
+  const int col_base = (MODE == MODE_L0_SWIGLU) ? col0 + wn * (NT * 16) : col0 + wn * (NT * 32);
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) {
+    __builtin_amdgcn_sched_barrier(0);   // one 32-row block at a time: keeps the address temporaries few
     {
-      const int m_in = lane_e & 31, half = lane_e >> 5;
+      const int m = lane_e & 31, half = lane_e >> 5;
+      const uint32_t row_addr = cbase + m * RB + half * 8;
+      const int sw = (m / RPB) & (NC - 1);
 #pragma unroll
-      for (int mt = 0; mt < MT; mt++) {
-        const int m = mt * 32 + m_in;
-        const uint32_t row_addr = cbase + m * RB + half * 8;
-        const int sw = (m / RPB) & (NC - 1);
+      for (int nt = 0; nt < OUT_NT; nt++) {
+        if (MODE == MODE_L0_GELU) __builtin_amdgcn_sched_barrier(0);  // bounds the live activation temporaries
 #pragma unroll
-        for (int nt = 0; nt < OUT_NT; nt++) {
-          if (MODE == MODE_L0_GELU) __builtin_amdgcn_sched_barrier(0);  // bounds the live activation temporaries
+        for (int qd = 0; qd < 4; qd++) {
+          float v[4];
 #pragma unroll
-          for (int q = 0; q < 4; q++) {
-            float v[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-              if (MODE == MODE_L0_SWIGLU) v[i] = silu(acc[mt][nt][q * 4 + i]) * acc[mt][nt + NT / 2][q * 4 + i];
-              else if (MODE == MODE_L0_GELU) v[i] = gelu_erf(acc[mt][nt][q * 4 + i]);
-              else v[i] = acc[mt][nt][q * 4 + i];
-            }
-            bf16x2 lo = {(__bf16)v[0], (__bf16)v[1]}, hi = {(__bf16)v[2], (__bf16)v[3]};
-            u32x2 pk = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-            const int chunk = nt * 4 + q;
-            *(u32x2 __attribute__((address_space(3)))*)(uintptr_t)(row_addr + ((chunk ^ sw) << 4)) = pk;
+          for (int i = 0; i < 4; i++) {
+            if (MODE == MODE_L0_SWIGLU) v[i] = silu(acc[mt][nt][qd * 4 + i]) * acc[mt][nt + NT / 2][qd * 4 + i];
+            else if (MODE == MODE_L0_GELU) v[i] = gelu_erf(acc[mt][nt][qd * 4 + i]);
+            else v[i] = acc[mt][nt][qd * 4 + i];
           }
+          bf16x2 lo = {(__bf16)v[0], (__bf16)v[1]}, hi = {(__bf16)v[2], (__bf16)v[3]};
+          u32x2 pk = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+          const int chunk = nt * 4 + qd;
+          *(u32x2 __attribute__((address_space(3)))*)(uintptr_t)(row_addr + ((chunk ^ sw) << 4)) = pk;
         }
       }
     }
     {
-      const int col_base = (MODE == MODE_L0_SWIGLU) ? col0 + wn * (NT * 16) : col0 + wn * (NT * 32);
       const int c = lane_e % NC;
 #pragma unroll
-      for (int it = 0; it < MT * 32 * NC / 64; it++) {
+      for (int it = 0; it < 32 * NC / 64; it++) {
         const int r = it * (64 / NC) + lane_e / NC;
         const u32x4 v = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
             cbase + r * RB + ((c ^ ((r / RPB) & (NC - 1))) << 4));
-        const int grow = wm * (MT * 32) + r;
+        const int grow = wm * (MT * 32) + mt * 32 + r;
         if (grow < nrows) *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v;
       }
     }
-    if (MODE == MODE_L1 && p.fused_combine) pending_panel = n_tile;
   }
+  if (MODE == MODE_L1 && p.fused_combine) pending_panel = n_tile;
+  // rows of A the next tile gathers (requested only now: held across the epilogue they push it into spilling)
+  if (next.idx >= 0) load_arows<MODE>(p, next, lane, w);
 }
 
 template <int MODE>
@@ -477,42 +578,43 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     if (p.fused_combine) combine_loop(p, &lds_slot[1]);
     return;
   }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int xcd = blockIdx.x & (kXcds - 1);
-  const int n_items = *p.n_items;
+  Queue q;
+  q.own_len = p.queue_len[xcd];
+  q.own_base = queue_pos(p, xcd, 0);
   int pending_panel = -1;   // layer1: column panel of the last finished tile, not yet published
-  if (tid == 0) lds_slot[0] = take_any(p, xcd, 0, n_items);
-  while (true) {
-    // also: every wavefront is done with the LDS stages of the previous tile before they are refilled
+
+  // first tile: found synchronously
+  Tile cur, next;
+  auto take_sync = [&](Tile& t) {
+    if (tid == 0) {
+      int idx = take_from(p, xcd, q.own_len, q.own_base);
+      if (idx < 0) idx = steal(p, xcd);
+      lds_slot[0] = idx;
+    }
     __syncthreads();
-    const int idx = lds_slot[0];
+    t.idx = uniform((int)lds_slot[0]);
     __syncthreads();
-    if (idx < 0) break;
-    const uint32_t it = p.items[idx];
-    if (it == 0xffffffffu) {   // a hole of the schedule
-      if (tid == 0) lds_slot[0] = take_any(p, xcd, 0, n_items);
+    if (t.idx >= 0) {
+      t.rec = load_item(p, t.idx);
+      load_arows<MODE>(p, t, lane, w);
+    }
+  };
+  take_sync(cur);
+  while (cur.idx >= 0) {
+    // every wavefront is done with the LDS of the previous tile before its slots are refilled
+    __syncthreads();
+    if (!segment_ready<MODE>(p, cur, lds_slot, true)) {
+      take_sync(cur);   // timed out (status says so): give the tile up and take another one
       continue;
     }
-    const int m_tile = it >> 12, n_tile = it & 0xfff;
-    if (MODE != MODE_L1 && p.seg_ready != nullptr) {
-      if (tid == 0) {
-        const bool ok = spin_until_ge(&p.seg_ready[p.tile_ready[m_tile]], p.ready_epoch, p.spin_limit);
-        if (!ok) {
-          atomicExch(p.status, (int)MOE_ERR_TIMEOUT);
-          lds_slot[0] = take_any(p, xcd, 0, n_items);   // skip this tile
-        }
-        lds_slot[1] = ok;
-      }
-      __syncthreads();
-      if (!lds_slot[1]) continue;
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
-    }
-    const int kind = p.tile_kind[m_tile];
-    if (kind == 2)
-      run_tile<2, 4, 4, MODE>(p, smem, lds_slot, m_tile, n_tile, xcd, n_items, pending_panel);
-    else if (kind == 1)
-      run_tile<2, 2, 4, MODE>(p, smem, lds_slot, m_tile, n_tile, xcd, n_items, pending_panel);
-    else
-      run_tile<1, 2, 2, MODE>(p, smem, lds_slot, m_tile, n_tile, xcd, n_items, pending_panel);
+    next.idx = -1;
+    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel);
+    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel);
+    else run_tile<1, 2, 2, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel);
+    cur = next;
   }
   if (MODE == MODE_L1 && pending_panel >= 0) publish_panel(p, pending_panel);
   if (MODE == MODE_L1 && p.fused_combine) combine_loop(p, &lds_slot[1]);

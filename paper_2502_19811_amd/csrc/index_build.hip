@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void k_index_scan(IndexParams p) {
     p.ws.status[3] = tb * p.n_tiles_n1;
     p.ws.status[4] = 0;
   }
-  if (threadIdx.x < 2 * kXcds) p.ws.status[8 + threadIdx.x] = 0;
+  if (threadIdx.x < 2 * kXcds) p.ws.status[8 + threadIdx.x] = 0;   // queue heads of both layers
   for (int i = threadIdx.x; i < p.n_tiles_n1; i += 256) p.ws.panel_done[i] = 0;
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += 256) {
@@ -238,11 +238,24 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileCap = 4096;  // tiles whose table fits the LDS copies of the schedule builder
 
+__device__ inline ItemRec make_item(const Workspace& ws, int m, int n) {
+  ItemRec r;
+  r.m_tile = m;
+  r.n_tile = n;
+  r.expert = ws.tile_expert[m];
+  r.row0 = ws.tile_row0[m];
+  r.nrows = ws.tile_rows[m];
+  r.kind = ws.tile_kind[m];
+  r.ready_seg = ws.tile_ready[m];
+  r.pad = 0;
+  return r;
+}
+
 // Layer0 items of the tiles order[lo..hi) (one height, expert-major), written from position base on.
 // ord / exp_of: LDS copies (or the global arrays when the table is too large).
 template <typename OrdT, typename ExpT>
-__device__ inline void emit_expert_major(uint32_t* items, const OrdT* ord, const ExpT* exp_of, int lo, int hi, int base,
-                                         int n_tiles_n, int tid, int nthreads) {
+__device__ inline void emit_expert_major(const Workspace& ws, ItemRec* items, const OrdT* ord, const ExpT* exp_of, int lo,
+                                         int hi, int base, int n_tiles_n, int tid, int nthreads) {
   // one (tile, group of 8 column tiles) pair per thread step
   const int n_groups = (n_tiles_n + 7) >> 3;
   for (int w = tid; w < (hi - lo) * n_groups; w += nthreads) {
@@ -254,18 +267,23 @@ __device__ inline void emit_expert_major(uint32_t* items, const OrdT* ord, const
     const int cnt = b - a;
     const int gw = min(8, n_tiles_n - g * 8);
     const int pos = base + (a - lo) * n_tiles_n + g * 8 * cnt + (i - a) * gw;
-    for (int n = 0; n < gw; n++) items[pos + n] = pack_item(ord[i], g * 8 + n);
+    ItemRec r = make_item(ws, ord[i], 0);
+    for (int n = 0; n < gw; n++) {
+      r.n_tile = g * 8 + n;
+      items[pos + n] = r;
+    }
   }
 }
 
 // Layer1 items of the tiles order[lo..hi): the tiles are dealt to the XCDs in contiguous chunks (an XCD then
-// keeps to few experts); XCD x's sequence is, per group of 4 column panels, its tiles, each with the 4 panels,
-// and sits at list positions seq * 8 + x from sequence index seq_base on.  Panel groups ascend, so all M-tiles
-// finish panel group g before g + 1 (Fig. 6).  Unused positions keep the no-op marker.
+// keeps to few experts); XCD x's queue continues, from position queue_pos[x] on, with its chunk swept per group of
+// 4 column panels: the chunk's tiles, each with the 4 panels.  Panel groups ascend, so all M-tiles of the chunk
+// finish panel group g before g + 1 (Fig. 6).
 template <typename OrdT>
-__device__ inline void emit_chunked(uint32_t* items, const OrdT* ord, int lo, int hi, int seq_base, int n_tiles_n,
-                                    int tid, int nthreads) {
+__device__ inline void emit_chunked(const Workspace& ws, ItemRec* items, const OrdT* ord, int lo, int hi,
+                                    const int32_t* queue_pos, int n_tiles_n, int tid, int nthreads) {
   const int nt = hi - lo;
+  if (nt == 0) return;
   const int chunk = (nt + kXcds - 1) / kXcds;
   const int n_groups = (n_tiles_n + 3) >> 2;
   for (int w = tid; w < nt * n_groups; w += nthreads) {
@@ -273,8 +291,12 @@ __device__ inline void emit_chunked(uint32_t* items, const OrdT* ord, int lo, in
     const int x = i / chunk, j = i % chunk;
     const int cnt = min(chunk, nt - x * chunk);
     const int gw = min(4, n_tiles_n - g * 4);
-    const int seq = seq_base + g * 4 * cnt + j * gw;
-    for (int n = 0; n < gw; n++) items[(seq + n) * kXcds + x] = pack_item(ord[lo + i], g * 4 + n);
+    const int pos = queue_pos[x] + g * 4 * cnt + j * gw;
+    ItemRec r = make_item(ws, ord[lo + i], 0);
+    for (int n = 0; n < gw; n++) {
+      r.n_tile = g * 4 + n;
+      items[pos + n] = r;
+    }
   }
 }
 
@@ -302,9 +324,6 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
       exp_lds[m] = (uint8_t)p.ws.tile_expert[m];
     }
   }
-  // layer1 list: no-op markers everywhere first (its holes stay that way)
-  const int n_items1_cap = (n_tiles + 3 * kXcds) * p.n_tiles_n1;
-  for (int i = tid; i < n_items1_cap; i += 1024) p.ws.items1[i] = 0xffffffffu;
   __syncthreads();
   auto key_of = [&](int m) {
     return in_lds ? (int)keys[m] : (2 - p.ws.tile_kind[m]) * nseg + (nseg > 1 ? p.ws.tile_ready[m] : 0);
@@ -339,12 +358,12 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   for (int c = 0; c < 3; c++) {
     const int lo = cls_first[c], hi = cls_first[c + 1];
     if (p.layer0_order == 0) {
-      if (in_lds) emit_expert_major(p.ws.items0, ord_lds, exp_lds, lo, hi, lo * p.n_tiles_n0, p.n_tiles_n0, tid, 1024);
-      else emit_expert_major(p.ws.items0, p.ws.tile_order, p.ws.tile_expert, lo, hi, lo * p.n_tiles_n0, p.n_tiles_n0, tid, 1024);
+      if (in_lds) emit_expert_major(p.ws, p.ws.items0, ord_lds, exp_lds, lo, hi, lo * p.n_tiles_n0, p.n_tiles_n0, tid, 1024);
+      else emit_expert_major(p.ws, p.ws.items0, p.ws.tile_order, p.ws.tile_expert, lo, hi, lo * p.n_tiles_n0, p.n_tiles_n0, tid, 1024);
     } else {
       for (int i = tid; i < (hi - lo) * p.n_tiles_n0; i += 1024) {
         const int m = in_lds ? (int)ord_lds[lo + i / p.n_tiles_n0] : p.ws.tile_order[lo + i / p.n_tiles_n0];
-        p.ws.items0[lo * p.n_tiles_n0 + i] = pack_item(m, i % p.n_tiles_n0);
+        p.ws.items0[lo * p.n_tiles_n0 + i] = make_item(p.ws, m, i % p.n_tiles_n0);
       }
     }
   }
@@ -361,14 +380,29 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
     }
     __syncthreads();
   }
-  int seq_base = 0;
+  // layer1: one contiguous queue per XCD; queue x holds its chunk of every height class, tallest first
+  __shared__ int32_t queue_pos[kXcds];
+  const int cap = (n_tiles + 3 * kXcds) / kXcds * p.n_tiles_n1;   // room per queue
+  if (tid < kXcds) queue_pos[tid] = tid * cap;
+  __syncthreads();
   for (int c = 0; c < 3; c++) {
     const int lo = cls_first[c], hi = cls_first[c + 1];
-    if (in_lds) emit_chunked(p.ws.items1, ord_lds, lo, hi, seq_base, p.n_tiles_n1, tid, 1024);
-    else emit_chunked(p.ws.items1, p.ws.tile_order, lo, hi, seq_base, p.n_tiles_n1, tid, 1024);
-    seq_base += (hi - lo + kXcds - 1) / kXcds * p.n_tiles_n1;
+    if (in_lds) emit_chunked(p.ws, p.ws.items1, ord_lds, lo, hi, queue_pos, p.n_tiles_n1, tid, 1024);
+    else emit_chunked(p.ws, p.ws.items1, p.ws.tile_order, lo, hi, queue_pos, p.n_tiles_n1, tid, 1024);
+    __syncthreads();
+    if (tid < kXcds) {
+      const int nt = hi - lo, chunk = (nt + kXcds - 1) / kXcds;
+      const int cnt = nt == 0 ? 0 : max(0, min(chunk, nt - tid * chunk));
+      queue_pos[tid] += cnt * p.n_tiles_n1;
+    }
+    __syncthreads();
   }
-  if (tid == 0) p.ws.status[3] = seq_base * kXcds;   // length of the layer1 list including its holes
+  if (tid < kXcds) {
+    const int n0 = n_tiles * p.n_tiles_n0;
+    p.ws.status[24 + tid] = tid < n0 ? (n0 - tid + kXcds - 1) / kXcds : 0;   // layer0: positions tid, tid + 8, ...
+    p.ws.status[32 + tid] = queue_pos[tid] - tid * cap;
+    p.ws.status[40 + tid] = tid * cap;
+  }
 }
 
 __global__ void k_tile_heights(const int32_t* __restrict__ kind, int32_t* __restrict__ height, int n) {

@@ -62,8 +62,8 @@ void layout(moe_plan* p) {
   p->off_tile_ready = take((size_t)p->max_tiles * 4);
   p->off_tile_kind = take((size_t)p->max_tiles * 4);
   p->off_tile_order = take((size_t)p->max_tiles * 4);
-  p->off_items0 = take((size_t)p->max_tiles * p->n_tiles_n0 * 4);
-  p->off_items1 = take((size_t)(p->max_tiles + 3 * kXcds) * p->n_tiles_n1 * 4);
+  p->off_items0 = take((size_t)p->max_tiles * p->n_tiles_n0 * sizeof(ItemRec));
+  p->off_items1 = take((size_t)(p->max_tiles + 3 * kXcds) * p->n_tiles_n1 * sizeof(ItemRec));
   p->off_panel_done = take((size_t)p->n_tiles_n1 * 4);
   p->off_h = take((size_t)s.R * s.F * 2);
   p->off_Y = take((size_t)s.R * s.H * 2);
@@ -86,8 +86,8 @@ Workspace view(const moe_plan* p, void* base) {
   w.tile_ready = (int32_t*)(b + p->off_tile_ready);
   w.tile_kind = (int32_t*)(b + p->off_tile_kind);
   w.tile_order = (int32_t*)(b + p->off_tile_order);
-  w.items0 = (uint32_t*)(b + p->off_items0);
-  w.items1 = (uint32_t*)(b + p->off_items1);
+  w.items0 = (ItemRec*)(b + p->off_items0);
+  w.items1 = (ItemRec*)(b + p->off_items1);
   w.panel_done = (uint32_t*)(b + p->off_panel_done);
   w.h = (uint16_t*)(b + p->off_h);
   w.Y = (uint16_t*)(b + p->off_Y);
@@ -308,11 +308,13 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     a.ldc = (uint32_t)s.F;
     a.K = s.H;
     a.items = ws.items0;
-    a.n_items = ws.status + 2;
     a.seg_ready = seg_ready;
     a.ready_epoch = ready_epoch;
     a.n_mfma = p->n_cu;
     a.queue_heads = ws.status + 8;
+    a.queue_len = ws.status + 24;
+    a.queue_base = nullptr;
+    a.queue_stride = kXcds;
     if (launch_layer0(a, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
 
@@ -331,7 +333,6 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.ldc = (uint32_t)s.H;
     b.K = s.F;
     b.items = ws.items1;
-    b.n_items = ws.status + 3;
     b.panel_done = ws.panel_done;
     int n_dm = fused ? (p->n_dm >= 0 ? p->n_dm : default_n_dm(s)) : 0;
     if (n_dm > p->n_cu - 8) n_dm = p->n_cu - 8;
@@ -342,6 +343,9 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.out = (uint16_t*)out;
     b.combine_counter = ws.status + 4;
     b.queue_heads = ws.status + 16;
+    b.queue_len = ws.status + 32;
+    b.queue_base = ws.status + 40;
+    b.queue_stride = 1;
     if (launch_layer1(b, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
   if (!mark(3)) return MOE_ERR_HIP;

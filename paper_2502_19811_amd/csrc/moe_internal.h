@@ -17,14 +17,18 @@ constexpr int kStages = 4;          // LDS stages in flight
 constexpr int kCombineChunk = 64;   // tokens per unit of combine work
 constexpr int kXcds = 8;            // XCDs of the device: workgroup i runs on XCD i % 8
 
-// Item of a GroupGEMM schedule: M-tile index in the high 20 bits, N-tile index in the low 12.
-__host__ __device__ inline uint32_t pack_item(uint32_t m_tile, uint32_t n_tile) { return (m_tile << 12) | n_tile; }
+// Item of a GroupGEMM schedule: one (M-tile, column tile) pair with the M-tile's table row copied in, so that a
+// workgroup needs a single 32-byte read to start on it.
+struct ItemRec {
+  int32_t m_tile, n_tile, expert, row0, nrows, kind, ready_seg, pad;
+};
 
 // Device-side view of the workspace (all pointers into the caller's workspace buffer).
 struct Workspace {
-  int32_t* status;        // [64]  0: device status word, 1: n_tiles, 2: n_items layer0, 3: n_items layer1,
-                          //       4: combine unit counter, 8..15: layer0 queue heads (one per XCD),
-                          //       16..23: layer1 queue heads
+  int32_t* status;        // [64]  0: device status word, 1: n_tiles, 2: items of layer0, 3: items of layer1,
+                          //       4: combine unit counter; per XCD: 8..15 layer0 queue heads, 16..23 layer1 queue
+                          //       heads, 24..31 layer0 queue lengths, 32..39 layer1 queue lengths, 40..47 layer1
+                          //       queue bases (layer0: queue x is list positions x, x+8, ...)
   int32_t* counts;        // [E]
   int32_t* offsets;       // [E+1]
   int32_t* perm;          // [R] sorted row -> pair id
@@ -37,8 +41,8 @@ struct Workspace {
   int32_t* tile_ready;    // [max_tiles] source segment the tile waits for
   int32_t* tile_kind;     // [max_tiles] 0 / 1 / 2: the tile is computed by the 64 / 128 / 256-row kernel variant
   int32_t* tile_order;    // [max_tiles] scratch of the schedule builder: tiles sorted tallest first
-  uint32_t* items0;       // [max_tiles * n_tiles_n0] layer0 schedule
-  uint32_t* items1;       // [max_tiles * n_tiles_n1] layer1 schedule
+  ItemRec* items0;        // [max_tiles * n_tiles_n0] layer0 schedule
+  ItemRec* items1;        // [(max_tiles + 24) * n_tiles_n1] layer1 schedule, one contiguous queue per XCD
   uint32_t* panel_done;   // [n_tiles_n1] finished M-tiles per column panel of layer1
   uint16_t* h;            // [R,F] bf16 activation buffer
   uint16_t* Y;            // [R,H] bf16 layer1 shared tensor
@@ -76,13 +80,15 @@ struct GemmParams {
   const int32_t* tile_rows;
   const int32_t* tile_ready;
   const int32_t* tile_kind;
-  const uint32_t* items;
-  const int32_t* n_items;   // device scalar
+  const ItemRec* items;
   const uint32_t* seg_ready;
   uint32_t ready_epoch;
   uint32_t spin_limit;
   int32_t* status;
-  int32_t* queue_heads;     // [8] next position of each XCD's share of the schedule
+  int32_t* queue_heads;     // [8] items already taken from each XCD's queue
+  const int32_t* queue_len; // [8] items in each XCD's queue
+  const int32_t* queue_base;// [8] list position of each queue's first item; nullptr: queue x starts at x
+  int32_t queue_stride;     // list positions between consecutive items of a queue
   // layer1 only
   uint32_t* panel_done;
   const int32_t* n_tiles;   // device scalar: M-tiles in total
