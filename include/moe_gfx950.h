@@ -130,6 +130,15 @@ int moe_get_tile_table(const moe_plan_t *plan, const void *workspace, int32_t *n
                        void *hip_stream);
 int32_t moe_plan_max_tiles(const moe_plan_t *plan);
 
+/* Stand-in for the peers on one GPU (for tests and the arrival experiment, Section 3.1.2 / Fig. 5): n_workgroups
+ * workgroups (1..64) on the given stream copy the plan's source segments, in index order, from staging into the
+ * receive buffer x (both dev bf16 [T,H]) at about gbytes_per_s in total (0 = unpaced), and after each segment
+ * store ready_epoch into seg_ready[s] (dev uint32 [S]) with a system-scope release.  seg_counters: dev uint32 [S],
+ * zero before the first call (the call leaves it zero).  Run a forward that waits on seg_ready on another stream,
+ * with "n_cu" at least n_workgroups below the device's compute units so that these workgroups find room. */
+int moe_play_arrival(const moe_plan_t *plan, const void *staging, void *x, uint32_t *seg_ready, uint32_t *seg_counters,
+                     uint32_t ready_epoch, double gbytes_per_s, int32_t n_workgroups, void *hip_stream);
+
 /* Average time in ms of the four phases (index build, layer0 kernel, layer1 kernel incl. fused combine,
  * stand-alone combine) over the forwards recorded since the last call (at most 64), from the events of the
  * "profile" option.  ms: host [4]; n_steps: host [1].  Waits for the recorded forwards to finish. */

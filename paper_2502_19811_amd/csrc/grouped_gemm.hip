@@ -219,14 +219,26 @@ __device__ __forceinline__ int queue_pos(const GemmParams& p, int x, int i) {
 }
 // Takes the next item of XCD x's queue; returns its list position or -1 when that queue is used up.
 __device__ __forceinline__ int take_from(const GemmParams& p, int x, int len, int base) {
+  if (len == 0) return -1;
   const int i = __hip_atomic_fetch_add(&p.queue_heads[x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return i < len ? base + i * p.queue_stride : -1;
 }
-// The other XCDs' leftovers, nearest first; -1 when every queue is used up.
+// The other XCDs' leftovers, nearest first; -1 when every queue is used up.  All heads and lengths are read first
+// (one round trip): at the end of a kernel, and in small problems, most queues are empty and an atomic on each
+// of them from every workgroup would serialise on the counters.
 __device__ __forceinline__ int steal(const GemmParams& p, int xcd) {
+  int head[kXcds], len[kXcds];
+#pragma unroll
   for (int d = 1; d < kXcds; d++) {
     const int x = (xcd + d) & (kXcds - 1);
-    const int idx = take_from(p, x, p.queue_len[x], queue_pos(p, x, 0));
+    head[d] = __hip_atomic_load(&p.queue_heads[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    len[d] = p.queue_len[x];
+  }
+#pragma unroll
+  for (int d = 1; d < kXcds; d++) {
+    if (head[d] >= len[d]) continue;
+    const int x = (xcd + d) & (kXcds - 1);
+    const int idx = take_from(p, x, len[d], queue_pos(p, x, 0));
     if (idx >= 0) return idx;
   }
   return -1;

@@ -416,6 +416,46 @@ hipError_t launch_tile_heights(const int32_t* kind, int32_t* height, int n, hipS
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Stand-in for the peers of Section 3.1.2 on one GPU: a few workgroups play all sources in turn, copying each source's
+// segment of token rows from a staging buffer into the receive buffer at a paced rate and then raising the
+// segment's ready flag (data first, system-scope release, then the flag), the way a peer's one-sided stores would.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_arrival_producer(const uint4* __restrict__ staging, uint4* __restrict__ x,
+                                                           ArrivalParams a) {
+  const long long t_start = wall_clock64();   // 100 MHz
+  long long sent = 0;                          // bytes (of all workgroups together) before the current chunk
+  const int nwg = gridDim.x, wg = blockIdx.x;
+  for (int s = 0; s < a.S; s++) {
+    const size_t lo = (size_t)a.seg_offsets[s] * a.row_bytes / 16, hi = (size_t)a.seg_offsets[s + 1] * a.row_bytes / 16;
+    for (size_t c = lo; c < hi; c += a.chunk16) {
+      const size_t end = c + a.chunk16 < hi ? c + a.chunk16 : hi;
+      // pace: this chunk may start once the bytes before it have had their time at the requested rate
+      if (a.bytes_per_us > 0) {
+        const long long due = t_start + (long long)((double)sent / a.bytes_per_us * 100.0);
+        while (wall_clock64() < due) __builtin_amdgcn_s_sleep(16);
+      }
+      for (size_t i = c + (size_t)wg * 1024 + threadIdx.x; i < end; i += (size_t)nwg * 1024) x[i] = staging[i];
+      sent += (long long)(end - c) * 16;
+    }
+    // the segment is there once every workgroup has written its share: the last one to arrive raises the flag
+    __threadfence_system();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const uint32_t arrived = __hip_atomic_fetch_add(&a.seg_arrived[s], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      if (arrived + 1 == (uint32_t)nwg) {
+        __hip_atomic_store(&a.seg_arrived[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        __hip_atomic_store(&a.seg_ready[s], a.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+  }
+}
+
+hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalParams& a, int n_wg, hipStream_t st) {
+  hipLaunchKernelGGL(k_arrival_producer, dim3(n_wg), dim3(1024), 0, st, (const uint4*)staging, (uint4*)x, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_index_build(const IndexParams& p, hipStream_t st) {
   if (p.s.R == 0) return hipSuccess;
   hipLaunchKernelGGL(k_index_hist, dim3(p.n_blocks), dim3(256), 0, st, p);

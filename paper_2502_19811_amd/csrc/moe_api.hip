@@ -416,6 +416,25 @@ int moe_get_tile_table(const moe_plan_t* p, const void* workspace, int32_t* n_ti
   return MOE_OK;
 }
 
+int moe_play_arrival(const moe_plan_t* p, const void* staging, void* x, uint32_t* seg_ready, uint32_t* seg_counters,
+                     uint32_t ready_epoch, double gbytes_per_s, int32_t n_workgroups, void* hip_stream) {
+  if (!p || !staging || !x || !seg_ready || !seg_counters) return MOE_ERR_INVALID_ARG;
+  if (!aligned16(staging) || !aligned16(x) || gbytes_per_s < 0 || n_workgroups < 1 || n_workgroups > 64)
+    return MOE_ERR_INVALID_ARG;
+  if (p->s.T == 0) return MOE_OK;
+  ArrivalParams a;
+  memset(&a, 0, sizeof(a));
+  a.S = p->s.S;
+  memcpy(a.seg_offsets, p->seg_offsets, sizeof(int32_t) * (p->s.S + 1));
+  a.row_bytes = (uint32_t)p->s.H * 2;
+  a.chunk16 = 64 * 1024 / 16;
+  a.bytes_per_us = gbytes_per_s * 1e3;
+  a.seg_ready = seg_ready;
+  a.seg_arrived = seg_counters;
+  a.epoch = ready_epoch;
+  return launch_arrival_producer(staging, x, a, n_workgroups, (hipStream_t)hip_stream) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 int moe_last_device_status(const moe_plan_t* p, const void* workspace, void* hip_stream) {
   if (!p || !workspace) return MOE_ERR_INVALID_ARG;
   Workspace ws = view(p, const_cast<void*>(workspace));

@@ -102,6 +102,17 @@ struct GemmParams {
   int32_t* combine_counter;
 };
 
+struct ArrivalParams {
+  int32_t S;
+  int32_t seg_offsets[kMaxSegments + 1];
+  uint32_t row_bytes;      // bytes of one token row
+  uint32_t chunk16;        // 16-byte units copied between two pacing checks
+  double bytes_per_us;     // 0: as fast as one workgroup copies
+  uint32_t* seg_ready;
+  uint32_t* seg_arrived;   // [S] workgroups done with each segment; zero between calls
+  uint32_t epoch;
+};
+
 struct CombineParams {
   const uint16_t* Y;
   const int32_t* inv_perm;
@@ -116,6 +127,7 @@ hipError_t launch_index_build(const IndexParams& p, hipStream_t st);
 hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st);
 hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalParams& a, int n_wg, hipStream_t st);
 hipError_t launch_tile_heights(const int32_t* kind, int32_t* height, int n, hipStream_t st);
 
 }  // namespace moe

@@ -110,3 +110,26 @@ def test_empty_batch_and_empty_experts():
     assert run.counts.tolist() == [0, 90, 90, 0, 0, 0]
     a, b = H.error_metrics(run.out, orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act))
     assert a <= H.REL_TOL and b <= H.REL_TOL
+
+
+def test_paced_arrival_by_a_producer_workgroup():
+    """The peers' stand-in fills the receive buffer segment by segment while the layer runs; same bits as resident."""
+    import paper_2502_19811_amd as moe
+    H, cfg, inp, ids, w, layer = _setup({"n_cu": 128, "spin_limit": 1 << 26, "layer0_order": 1})
+    layer.forward(); base = layer.results()
+    staging = layer.x.clone()
+    layer.x.zero_()
+    layer.out.zero_()
+    flags = torch.zeros(cfg.S, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    print("producer + forward", flush=True)
+    counters = torch.zeros(cfg.S, dtype=torch.int32, device="cuda")
+    moe.moe_play_arrival(layer.plan, staging, layer.x, flags, counters, 3, 2.0, 3, side)   # 1 MB at 2 GB/s: 0.5 ms
+    layer.forward(seg_ready=flags, epoch=3)
+    side.synchronize()
+    run = layer.results()
+    layer.close()
+    assert run.status == 0
+    assert flags.cpu().tolist() == [3] * cfg.S and counters.cpu().tolist() == [0] * cfg.S
+    np.testing.assert_array_equal(run.out, base.out)

@@ -49,6 +49,7 @@ class MoEConfig:
     seed: int
     skew_zipf: float = 0.0        # >0: add log((e+1)^-s / Z) to the logits
     dirichlet_segments: bool = False
+    load_std: float = 0.0         # >0: expert popularity with this standard deviation of the per-expert fractions
 
     @property
     def R(self) -> int:
@@ -72,6 +73,21 @@ CONFIGS: Dict[str, MoEConfig] = {
     "skewed": MoEConfig("skewed", T=32768, H=4096, F=14336, E=8, k=2, act=ACT_SWIGLU, S=8, seed=4,
                         skew_zipf=1.2, dirichlet_segments=True),
 }
+
+
+# Further shapes of the paper's evaluation, for the rows marked "next": Table 2's Qwen2-MoE-2.7B row, the
+# tensor-parallel slices of the Mixtral expert (Fig. 12: F/TP columns per GPU) and the token-distribution study
+# of Fig. 14 (std of the per-expert load fractions; 0.032 is the production average the paper quotes).
+CONFIGS.update({
+    "qwen2_table2": MoEConfig("qwen2_table2", T=8192, H=2048, F=1408, E=64, k=4, act=ACT_SWIGLU, S=8, seed=5),
+    "mixtral_tp2": MoEConfig("mixtral_tp2", T=8192, H=4096, F=7168, E=8, k=2, act=ACT_SWIGLU, S=8, seed=6),
+    "mixtral_tp4": MoEConfig("mixtral_tp4", T=8192, H=4096, F=3584, E=8, k=2, act=ACT_SWIGLU, S=8, seed=7),
+    "mixtral_tp8": MoEConfig("mixtral_tp8", T=8192, H=4096, F=1792, E=8, k=2, act=ACT_SWIGLU, S=8, seed=8),
+    "mixtral_std032": MoEConfig("mixtral_std032", T=8192, H=4096, F=14336, E=8, k=2, act=ACT_SWIGLU, S=8, seed=9,
+                                load_std=0.032),
+    "mixtral_std05": MoEConfig("mixtral_std05", T=8192, H=4096, F=14336, E=8, k=2, act=ACT_SWIGLU, S=8, seed=10,
+                               load_std=0.05),
+})
 
 
 def f32_to_bf16(a: np.ndarray) -> np.ndarray:
@@ -161,6 +177,14 @@ def gate_logits(cfg: MoEConfig, threads: int = 8) -> np.ndarray:
         pop = np.arange(1, cfg.E + 1, dtype=np.float64) ** (-cfg.skew_zipf)
         pop /= pop.sum()
         g += np.log(pop).astype(np.float32)[None, :]
+    if cfg.load_std > 0.0:
+        # per-expert bias that spreads the popularity linearly around 1/E.  Top-2 routing over 8 experts amplifies
+        # the spread of the bias by about 1/0.78 (measured), hence the factor: the realised standard deviation of
+        # the per-expert load fractions then lands within a few percent of load_std
+        ramp = np.linspace(-1.0, 1.0, cfg.E)
+        frac = 1.0 / cfg.E + 0.78 * cfg.load_std * ramp / ramp.std()
+        frac = np.clip(frac, 1e-3, None)
+        g += np.log(frac / frac.sum()).astype(np.float32)[None, :]
     return g
 
 
