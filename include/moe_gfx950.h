@@ -66,8 +66,9 @@ int moe_plan_destroy(moe_plan_t *plan);
  *   "tile_m"       64 / 128 / 256: rows of the tallest GroupGEMM tile (default: chosen from T*k/E)
  *   "n_dm"         data-movement workgroups of the layer1 kernel (default: table lookup per shape)
  *   "layer1_order" 1 = finished column panels (Fig. 6) are reduced inside the layer1 kernel, by its n_dm
- *                  data-movement workgroups and by GEMM workgroups that ran out of tiles (default);
- *                  0 = a separate combine kernel after the layer1 kernel
+ *                  data-movement workgroups and by GEMM workgroups that ran out of tiles;
+ *                  0 = a separate combine kernel after the layer1 kernel (default: the faster one on
+ *                  every workload measured, see paper_2502_19811_amd/split_sweep.py)
  *   "layer0_order" 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5)
  *   "spin_limit"   >0: a wait on a ready flag gives up after that many polls and the forward
  *                  reports MOE_ERR_TIMEOUT through moe_last_device_status (0 = wait for ever)

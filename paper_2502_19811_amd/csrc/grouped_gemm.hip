@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 enum { MODE_L0_GELU = 0, MODE_L0_SWIGLU = 1, MODE_L1 = 2 };
 
 constexpr int BK = kTileK, NS = kStages, BN = kTileN;
+constexpr int kMaxPanels = 128;   // column panels whose publication can be batched per workgroup
 constexpr int B_STAGE = BK * BN * 2;  // 16 KiB
 
 __device__ __forceinline__ bf16x8 lds_read_a(uint32_t addr) {
@@ -97,72 +98,92 @@ __device__ __forceinline__ bool spin_until_ge(const uint32_t* flag, uint32_t wan
 template <int K>
 __device__ __forceinline__ void combine_unit_k(const GemmParams& p, int panel, int chunk, int k_runtime) {
   constexpr int KK = K > 0 ? K : 1;
-  constexpr int TB = K == 0 ? 1 : (K <= 2 ? 8 : (K <= 4 ? 4 : 2));   // tokens in flight per thread
+  constexpr int TB = K == 0 ? 1 : (K <= 2 ? 8 : (K <= 4 ? 4 : 2));   // tokens per batch of a thread
+  constexpr int NB = kCombineChunk / 8 / TB;                           // batches per unit
   const int tid = threadIdx.x;
   const int cg = tid & 31, ts = tid >> 5;
   const size_t col = (size_t)panel * BN + cg * 8;
-  const int k = K > 0 ? K : k_runtime;
-#pragma unroll 1
-  for (int i0 = 0; i0 < kCombineChunk / 8; i0 += TB) {
-    int t[TB];
-    float acc[TB][8];
+  if (K == 0) {
+    // any other k: one token at a time
+    for (int i0 = 0; i0 < kCombineChunk / 8; i0++) {
+      const int t = chunk * kCombineChunk + i0 * 8 + ts;
+      if (t >= p.T) continue;
+      float acc[8];
 #pragma unroll
-    for (int b = 0; b < TB; b++) {
-      t[b] = chunk * kCombineChunk + (i0 + b) * 8 + ts;
+      for (int c = 0; c < 8; c++) acc[c] = 0.f;
+      for (int j = 0; j < k_runtime; j++) {
+        const int row = p.inv_perm[t * k_runtime + j];
+        const float w = p.topk_weights[t * k_runtime + j];
+        const u32x4 v = *(const u32x4*)(p.C + (size_t)row * p.ldc + col);
 #pragma unroll
-      for (int c = 0; c < 8; c++) acc[b][c] = 0.f;
-    }
-    if (K > 0) {
-      int row[TB][KK];
-      float w[TB][KK];
-      u32x4 v[TB][KK];
-#pragma unroll
-      for (int b = 0; b < TB; b++) {
-        const int tt = t[b] < p.T ? t[b] : p.T - 1;
-#pragma unroll
-        for (int j = 0; j < KK; j++) {
-          row[b][j] = p.inv_perm[tt * KK + j];
-          w[b][j] = p.topk_weights[tt * KK + j];
+        for (int c = 0; c < 4; c++) {
+          acc[2 * c] += w * __uint_as_float(v[c] << 16);
+          acc[2 * c + 1] += w * __uint_as_float(v[c] & 0xffff0000u);
         }
       }
-#pragma unroll
-      for (int b = 0; b < TB; b++)
-#pragma unroll
-        for (int j = 0; j < KK; j++) v[b][j] = *(const u32x4*)(p.C + (size_t)row[b][j] * p.ldc + col);
-#pragma unroll
-      for (int b = 0; b < TB; b++)
-#pragma unroll
-        for (int j = 0; j < KK; j++)
-#pragma unroll
-          for (int c = 0; c < 4; c++) {
-            acc[b][2 * c] += w[b][j] * __uint_as_float(v[b][j][c] << 16);
-            acc[b][2 * c + 1] += w[b][j] * __uint_as_float(v[b][j][c] & 0xffff0000u);
-          }
-    } else {
-      if (t[0] < p.T) {
-        for (int j = 0; j < k; j++) {
-          const int row = p.inv_perm[t[0] * k + j];
-          const float w = p.topk_weights[t[0] * k + j];
-          const u32x4 v = *(const u32x4*)(p.C + (size_t)row * p.ldc + col);
-#pragma unroll
-          for (int c = 0; c < 4; c++) {
-            acc[0][2 * c] += w * __uint_as_float(v[c] << 16);
-            acc[0][2 * c + 1] += w * __uint_as_float(v[c] & 0xffff0000u);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int b = 0; b < TB; b++) {
-      if (t[b] >= p.T) continue;
       u32x4 o;
 #pragma unroll
       for (int c = 0; c < 4; c++) {
-        bf16x2 pr = {(__bf16)acc[b][2 * c], (__bf16)acc[b][2 * c + 1]};
+        bf16x2 pr = {(__bf16)acc[2 * c], (__bf16)acc[2 * c + 1]};
         o[c] = __builtin_bit_cast(uint32_t, pr);
       }
-      *(u32x4*)(p.out + (size_t)t[b] * p.H + col) = o;
+      *(u32x4*)(p.out + (size_t)t * p.H + col) = o;
     }
+    return;
+  }
+  // Two batches in flight: the rows of batch i+1 are requested before batch i is summed and stored.
+  float w[2][TB][KK];
+  u32x4 v[2][TB][KK];
+  auto request = [&](int buf, int batch) {
+    int row[TB][KK];
+#pragma unroll
+    for (int b = 0; b < TB; b++) {
+      const int t = chunk * kCombineChunk + (batch * TB + b) * 8 + ts;
+      const int tt = t < p.T ? t : p.T - 1;
+#pragma unroll
+      for (int j = 0; j < KK; j++) {
+        row[b][j] = p.inv_perm[tt * KK + j];
+        w[buf][b][j] = p.topk_weights[tt * KK + j];
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < TB; b++)
+#pragma unroll
+      for (int j = 0; j < KK; j++) v[buf][b][j] = *(const u32x4*)(p.C + (size_t)row[b][j] * p.ldc + col);
+  };
+  auto finish = [&](int buf, int batch) {
+#pragma unroll
+    for (int b = 0; b < TB; b++) {
+      const int t = chunk * kCombineChunk + (batch * TB + b) * 8 + ts;
+      float acc[8];
+#pragma unroll
+      for (int c = 0; c < 8; c++) acc[c] = 0.f;
+#pragma unroll
+      for (int j = 0; j < KK; j++)
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+          acc[2 * c] += w[buf][b][j] * __uint_as_float(v[buf][b][j][c] << 16);
+          acc[2 * c + 1] += w[buf][b][j] * __uint_as_float(v[buf][b][j][c] & 0xffff0000u);
+        }
+      if (t < p.T) {
+        u32x4 o;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+          bf16x2 pr = {(__bf16)acc[2 * c], (__bf16)acc[2 * c + 1]};
+          o[c] = __builtin_bit_cast(uint32_t, pr);
+        }
+        *(u32x4*)(p.out + (size_t)t * p.H + col) = o;
+      }
+    }
+  };
+  static_assert(NB % 2 == 0, "batches are processed in pairs");
+  request(0, 0);
+#pragma unroll 1
+  for (int i = 0; i < NB; i += 2) {
+    request(1, i + 1);
+    finish(0, i);
+    if (i + 2 < NB) request(0, i + 2);
+    finish(1, i + 1);
   }
 }
 
@@ -177,17 +198,32 @@ __device__ __forceinline__ void combine_unit(const GemmParams& p, int panel, int
 }
 
 // Claims combine units until none are left.  A unit of panel n may start once every M-tile of that panel is done.
-__device__ __forceinline__ void combine_loop(const GemmParams& p, int32_t* lds_slot) {
+// all_at_once: the panels are all published together at the end of the GEMM work (no data-movement workgroups), so
+// the workgroup waits for the last panel once and needs a single acquire instead of one per panel.
+__device__ __forceinline__ void combine_loop(const GemmParams& p, int32_t* lds_slot, bool all_at_once) {
   const int n_panels = p.H / BN;
   const int n_chunks = (p.T + kCombineChunk - 1) / kCombineChunk;
   const int total = n_panels * n_chunks;
   const uint32_t need = (uint32_t)*p.n_tiles;
   int acquired_panel = -1;
+  if (all_at_once) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      bool ok = true;
+      for (int n = 0; n < n_panels && ok; n++) ok = spin_until_ge(&p.panel_done[n], need, p.spin_limit);
+      if (!ok) atomicExch(p.status, (int)MOE_ERR_TIMEOUT);
+      *lds_slot = ok;
+    }
+    __syncthreads();
+    if (!*lds_slot) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    acquired_panel = n_panels;   // everything is acquired
+  }
   while (true) {
     __syncthreads();
     if (threadIdx.x == 0) {
       int u = atomicAdd(p.combine_counter, 1);
-      if (u < total) {
+      if (u < total && !all_at_once) {
         const int panel = u / n_chunks;
         if (panel != acquired_panel && !spin_until_ge(&p.panel_done[panel], need, p.spin_limit)) {
           atomicExch(p.status, (int)MOE_ERR_TIMEOUT);
@@ -200,7 +236,7 @@ __device__ __forceinline__ void combine_loop(const GemmParams& p, int32_t* lds_s
     const int u = *lds_slot;
     if (u >= total) break;
     const int panel = u / n_chunks;
-    if (panel != acquired_panel) {
+    if (!all_at_once && panel != acquired_panel) {
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       acquired_panel = panel;
     }
@@ -363,7 +399,8 @@ __device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t
 // epilogue.  next.idx = -1: no further tile.
 template <int WM, int MT, int NT, int MODE>
 __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, const Tile& cur,
-                                         Tile& next, int xcd, const Queue& q, int& pending_panel) {
+                                         Tile& next, int xcd, const Queue& q, int& pending_panel,
+                                         volatile int32_t* lds_panel_count_ptr) {
   constexpr int WN = 4 / WM;
   constexpr int BM = WM * MT * 32;
   static_assert(WN * NT * 32 == BN, "tile must be 256 columns wide");
@@ -576,7 +613,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       }
     }
   }
-  if (MODE == MODE_L1 && p.fused_combine) pending_panel = n_tile;
+  if (MODE == MODE_L1 && p.fused_combine) {
+    if (p.batch_publish) {
+      if (tid == 0) lds_panel_count_ptr[n_tile] += 1;
+    } else {
+      pending_panel = n_tile;
+    }
+  }
   // rows of A the next tile gathers (requested only now: held across the epilogue they push it into spilling)
   if (next.idx >= 0) load_arows<MODE>(p, next, lane, w);
 }
@@ -585,9 +628,13 @@ template <int MODE>
 __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int32_t lds_slot[2];
+  __shared__ int32_t lds_panel_count[kMaxPanels];   // layer1, batched publication: tiles finished per column panel
   const int tid = threadIdx.x;
+  if (MODE == MODE_L1) {
+    for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
+  }
   if (MODE == MODE_L1 && (int)blockIdx.x >= p.n_mfma) {
-    if (p.fused_combine) combine_loop(p, &lds_slot[1]);
+    if (p.fused_combine) combine_loop(p, &lds_slot[1], false);
     return;
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
@@ -623,13 +670,24 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
       continue;
     }
     next.idx = -1;
-    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel);
-    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel);
-    else run_tile<1, 2, 2, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel);
+    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count);
+    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count);
+    else run_tile<1, 2, 2, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count);
     cur = next;
   }
-  if (MODE == MODE_L1 && pending_panel >= 0) publish_panel(p, pending_panel);
-  if (MODE == MODE_L1 && p.fused_combine) combine_loop(p, &lds_slot[1]);
+  if (MODE == MODE_L1 && p.fused_combine) {
+    if (p.batch_publish) {
+      // no data-movement workgroup is waiting for single tiles: one release for everything this workgroup wrote
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __syncthreads();
+      for (int i = tid; i < p.H / BN; i += 256)
+        if (lds_panel_count[i] > 0)
+          __hip_atomic_fetch_add(&p.panel_done[i], (uint32_t)lds_panel_count[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (pending_panel >= 0) {
+      publish_panel(p, pending_panel);
+    }
+    combine_loop(p, &lds_slot[1], p.batch_publish != 0);
+  }
 }
 
 template <int MODE>

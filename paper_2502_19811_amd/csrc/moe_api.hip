@@ -141,7 +141,7 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
   p->tile_m = default_tile_m(p->s);
   p->n_dm = -1;
   p->layer0_order = 0;
-  p->layer1_order = 1;
+  p->layer1_order = 0;   // measured faster on every workload so far: see the sweep tool and default_n_dm
   p->spin_limit = 0;
   p->phases = 15;
   p->n_cu = 0;
@@ -338,6 +338,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     if (n_dm > p->n_cu - 8) n_dm = p->n_cu - 8;
     b.n_mfma = p->n_cu - n_dm;
     b.fused_combine = fused ? 1 : 0;
+    b.batch_publish = (fused && n_dm == 0 && s.H / kTileN <= 128) ? 1 : 0;
     b.inv_perm = ws.inv_perm;
     b.topk_weights = topk_weights;
     b.out = (uint16_t*)out;

@@ -14,7 +14,7 @@ constexpr int kIndexChunk = 1024;   // (token, slot) pairs handled by one workgr
 constexpr int kTileN = 256;         // columns of B staged per GroupGEMM tile
 constexpr int kTileK = 32;          // depth of one LDS stage
 constexpr int kStages = 4;          // LDS stages in flight
-constexpr int kCombineChunk = 64;   // tokens per unit of combine work
+constexpr int kCombineChunk = 256;  // tokens per unit of combine work
 constexpr int kXcds = 8;            // XCDs of the device: workgroup i runs on XCD i % 8
 
 // Item of a GroupGEMM schedule: one (M-tile, column tile) pair with the M-tile's table row copied in, so that a
@@ -94,6 +94,7 @@ struct GemmParams {
   const int32_t* n_tiles;   // device scalar: M-tiles in total
   int32_t n_mfma;           // workgroups doing GEMM tiles; the rest are data-movement workgroups
   int32_t fused_combine;    // 1: data-movement workgroups reduce finished panels inside this kernel
+  int32_t batch_publish;    // 1: no data-movement workgroups: a GEMM workgroup publishes all its tiles at its end
   // combine
   const int32_t* inv_perm;
   const float* topk_weights;

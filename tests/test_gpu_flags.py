@@ -27,7 +27,8 @@ def test_output_is_deterministic_and_independent_of_the_schedule():
     ref = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
     a, b = H.error_metrics(base.out, ref)
     assert a <= H.REL_TOL and b <= H.REL_TOL
-    for opts in ({}, {"layer0_order": 1}, {"layer1_order": 0}, {"n_dm": 16}, {"tile_m": 128}, {"n_cu": 64}):
+    for opts in ({}, {"layer0_order": 1}, {"layer1_order": 1}, {"layer1_order": 1, "n_dm": 16}, {"tile_m": 128},
+                 {"n_cu": 64}):
         print(f"options {opts}", flush=True)
         _, _, _, _, _, l2 = _setup(opts)
         l2.forward(); r2 = l2.results(); l2.close()
