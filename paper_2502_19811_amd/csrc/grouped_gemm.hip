@@ -294,6 +294,7 @@ struct Tile {
   int idx;        // list position, -1: none
   ItemRec rec;
   int arow[4];    // rows of A this lane loads per stage (layer0: gathered token rows, layer1: rows of h)
+  int pre;        // 1: the loads of its first NS-1 stages were issued during the previous tile's epilogue
 };
 __device__ __forceinline__ ItemRec make_uniform(ItemRec r) {
   r.m_tile = uniform(r.m_tile); r.n_tile = uniform(r.n_tile); r.expert = uniform(r.expert); r.row0 = uniform(r.row0);
@@ -327,7 +328,7 @@ __device__ __forceinline__ void load_arows(const GemmParams& p, Tile& t, int lan
 // Address set-up of a tile and the loads of its first NS-1 stages.
 template <int WM, int MT, int NT, int MODE>
 __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t lds0, const Tile& t, LoadState& ls, int lane,
-                                                int w) {
+                                                int w, bool issue) {
   constexpr int BM = WM * MT * 32;
   constexpr int A_STAGE = BM * BK * 2;
   constexpr int STAGE = A_STAGE + B_STAGE;
@@ -359,14 +360,19 @@ __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t ld
   ls.Ab = uniform(p.A);
   ls.Bb = uniform(p.B + (uint64_t)t.rec.expert * p.b_expert_bytes);
   const size_t bstep = (size_t)BK * p.ldb * 2;
+  if (issue) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; s++) {
+    for (int s = 0; s < NS - 1; s++) {
 #pragma unroll
-    for (int j = 0; j < LA; j++) dma16(ls.Ab, ls.aoff[j], lds0 + s * STAGE + (w * LA + j) * 1024);
+      for (int j = 0; j < LA; j++) dma16(ls.Ab, ls.aoff[j], lds0 + s * STAGE + (w * LA + j) * 1024);
 #pragma unroll
-    for (int j = 0; j < LB; j++) dma16(ls.Bb, ls.boff[j], lds0 + s * STAGE + A_STAGE + (w * LB + j) * 1024);
-    ls.Ab += BK * 2;
-    ls.Bb += bstep;
+      for (int j = 0; j < LB; j++) dma16(ls.Bb, ls.boff[j], lds0 + s * STAGE + A_STAGE + (w * LB + j) * 1024);
+      ls.Ab += BK * 2;
+      ls.Bb += bstep;
+    }
+  } else {
+    ls.Ab += (NS - 1) * BK * 2;
+    ls.Bb += (NS - 1) * bstep;
   }
 }
 
@@ -400,7 +406,7 @@ __device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t
 template <int WM, int MT, int NT, int MODE>
 __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, const Tile& cur,
                                          Tile& next, int xcd, const Queue& q, int& pending_panel,
-                                         volatile int32_t* lds_panel_count_ptr) {
+                                         volatile int32_t* lds_panel_count_ptr, volatile uint32_t* lds_mask) {
   constexpr int WN = 4 / WM;
   constexpr int BM = WM * MT * 32;
   static_assert(WN * NT * 32 == BN, "tile must be 256 columns wide");
@@ -437,7 +443,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   }
   // address set-up and the loads of the first NS-1 stages
   LoadState ls;
-  setup_and_issue<WM, MT, NT, MODE>(p, lds0, cur, ls, lane, w);
+  setup_and_issue<WM, MT, NT, MODE>(p, lds0, cur, ls, lane, w, !cur.pre);
   const char* Ab = uniform(ls.Ab);
   const char* Bb = uniform(ls.Bb);
   const size_t bstep = (size_t)BK * p.ldb * 2;
@@ -498,6 +504,14 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // operand loads of the first stages were issued before (by the previous tile, or by the kernel for the first).
   int next_raw = 0;
   if (tid == 0) next_raw = take_from(p, xcd, q.own_len, q.own_base);
+  // Full-height tiles start the loads of a full-height successor during their own epilogue, which needs the
+  // successor's segment to be there already: the ready flags are sampled here (lane s of the first wavefront reads
+  // flag s) and looked at when the successor is known.  A flag raised later than this only costs the early start.
+  constexpr bool kCanPre = WM == 2 && MT == 4 && MODE != MODE_L0_GELU;   // (the GELU variant has no registers left for it)
+  const bool flags_on = MODE != MODE_L1 && p.seg_ready != nullptr;
+  uint32_t flag_v = 0;
+  if (kCanPre && flags_on && tid < p.n_segments)
+    flag_v = __hip_atomic_load(&p.seg_ready[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 
   const int nk = p.K / BK;  // >= NS - 1 (checked on the host)
   // first stage landed?  Everything issued after it (two more stages, and whatever the previous tile's epilogue
@@ -535,12 +549,20 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // behind them: thread 0 turns its queue ticket into a list position (stealing from other XCDs if its own queue is
   // used up) and hands it to the workgroup across the barrier; everybody then asks for the item record, whose
   // latency the remaining 48 MFMAs cover.
+  uint64_t ready_mask = ~0ull;
+  if (kCanPre && flags_on) ready_mask = __ballot(tid < p.n_segments && flag_v >= p.ready_epoch);
   if (tid == 0) {
     if (next_raw < 0) next_raw = steal(p, xcd);
     lds_slot[0] = next_raw;
+    if (kCanPre && flags_on) {
+      lds_mask[0] = (uint32_t)ready_mask;
+      lds_mask[1] = (uint32_t)(ready_mask >> 32);
+    }
   }
   block_barrier();
   next.idx = uniform((int)lds_slot[0]);
+  if (kCanPre && flags_on)
+    ready_mask = (uint32_t)uniform((int)lds_mask[0]) | ((uint64_t)(uint32_t)uniform((int)lds_mask[1]) << 32);
   ItemRec raw_rec;
   if (next.idx >= 0) raw_rec = p.items[next.idx];
   half2(0, false, ((kt + 1) % NS) * STAGE);
@@ -561,6 +583,12 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   block_barrier();   // every wavefront is done reading the operand stages
 
   if (next.idx >= 0) next.rec = make_uniform(raw_rec);
+  // early start of the successor (see above): its gather rows are requested now, its first stages after the first
+  // 32-row block of the epilogue, into the three stages the epilogue does not use
+  bool do_pre = false;
+  if (kCanPre && next.idx >= 0 && next.rec.kind == 2 && ((ready_mask >> (next.rec.ready_seg & 63)) & 1)) do_pre = true;
+  next.pre = do_pre;
+  if (kCanPre && do_pre) load_arows<MODE>(p, next, lane, w);
 
   // Epilogue.  The MFMAs ran with the operands swapped (B fragment first), so a lane holds, for output row
   // lane & 31 of each 32x32 block, the columns 8*(i/4) + 4*(lane/32) + i%4: four consecutive columns per group of
@@ -612,6 +640,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
         if (grow < nrows) *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v;
       }
     }
+    if constexpr (kCanPre) {
+      if (mt == 0 && do_pre) {
+        if (flags_on) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+        LoadState ls_next;
+        setup_and_issue<WM, MT, NT, MODE>(p, lds0, next, ls_next, lane_e, w, true);
+      }
+    }
   }
   if (MODE == MODE_L1 && p.fused_combine) {
     if (p.batch_publish) {
@@ -621,13 +656,14 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     }
   }
   // rows of A the next tile gathers (requested only now: held across the epilogue they push it into spilling)
-  if (next.idx >= 0) load_arows<MODE>(p, next, lane, w);
+  if (next.idx >= 0 && !do_pre) load_arows<MODE>(p, next, lane, w);
 }
 
 template <int MODE>
 __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int32_t lds_slot[2];
+  __shared__ uint32_t lds_mask[2];
   __shared__ int32_t lds_panel_count[kMaxPanels];   // layer1, batched publication: tiles finished per column panel
   const int tid = threadIdx.x;
   if (MODE == MODE_L1) {
@@ -655,6 +691,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     }
     __syncthreads();
     t.idx = uniform((int)lds_slot[0]);
+    t.pre = 0;
     __syncthreads();
     if (t.idx >= 0) {
       t.rec = load_item(p, t.idx);
@@ -665,14 +702,14 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   while (cur.idx >= 0) {
     // every wavefront is done with the LDS of the previous tile before its slots are refilled
     __syncthreads();
-    if (!segment_ready<MODE>(p, cur, lds_slot, true)) {
+    if (!cur.pre && !segment_ready<MODE>(p, cur, lds_slot, true)) {
       take_sync(cur);   // timed out (status says so): give the tile up and take another one
       continue;
     }
     next.idx = -1;
-    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count);
-    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count);
-    else run_tile<1, 2, 2, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count);
+    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+    else run_tile<1, 2, 2, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
     cur = next;
   }
   if (MODE == MODE_L1 && p.fused_combine) {

@@ -310,6 +310,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     a.items = ws.items0;
     a.seg_ready = seg_ready;
     a.ready_epoch = ready_epoch;
+    a.n_segments = s.S;
     a.n_mfma = p->n_cu;
     a.queue_heads = ws.status + 8;
     a.queue_len = ws.status + 24;

@@ -83,6 +83,7 @@ struct GemmParams {
   const ItemRec* items;
   const uint32_t* seg_ready;
   uint32_t ready_epoch;
+  int32_t n_segments;       // entries of seg_ready
   uint32_t spin_limit;
   int32_t* status;
   int32_t* queue_heads;     // [8] items already taken from each XCD's queue
