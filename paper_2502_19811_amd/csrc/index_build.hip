@@ -81,9 +81,6 @@ __global__ __launch_bounds__(256) void k_index_hist(IndexParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 2 (one workgroup): expert counts and offsets, per-workgroup bases, the M-tile table, and
-// the counters of this forward reset to zero.
-//
 // Tiling of an expert's rows: as many tiles of tile_m rows as fit, then the remainder is cut so that little
 // of a tile is padding: with tile_m = 256 a remainder of up to 64 rows becomes one 64-row tile, up to 128 one
 // 128-row tile, up to 192 a 128-row and a 64-row tile, more one ragged 256-row tile (tile_m = 128: 64 or 128).
@@ -99,80 +96,96 @@ __device__ inline int tail_tiles(int rem, int tile_m, int* h0, int* h1) {
   return 1;
 }
 
-__global__ __launch_bounds__(256) void k_index_scan(IndexParams p) {
-  __shared__ int32_t cnt[kMaxExperts];
-  __shared__ int32_t off[kMaxExperts + 1];
-  __shared__ int32_t tbase[kMaxExperts + 1];
-  const int E = p.s.E;
-  for (int e = threadIdx.x; e < E; e += 256) {
-    int run = 0;
-    for (int b = 0; b < p.n_blocks; b++) {
-      int c = p.ws.block_hist[b * E + e];
-      p.ws.block_hist[b * E + e] = run;   // rows of expert e that come from earlier workgroups
-      run += c;
-    }
-    cnt[e] = run;
-  }
+// Exclusive prefix sum over 256 values in LDS (one per thread of the workgroup); returns the total.
+__device__ inline int exclusive_scan_256(int32_t* buf, int v) {
+  const int t = threadIdx.x;
+  buf[t] = v;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int o = 0, tb = 0;
-    for (int e = 0; e < E; e++) {
-      off[e] = o;
-      tbase[e] = tb;
-      o += cnt[e];
-      int h0 = 0, h1 = 0;
-      tb += cnt[e] / p.tile_m + tail_tiles(cnt[e] % p.tile_m, p.tile_m, &h0, &h1);
-    }
-    off[E] = o;
-    tbase[E] = tb;
-    p.ws.status[0] = 0;
-    p.ws.status[1] = tb;
-    p.ws.status[2] = tb * p.n_tiles_n0;
-    p.ws.status[3] = tb * p.n_tiles_n1;
-    p.ws.status[4] = 0;
+  for (int d = 1; d < 256; d <<= 1) {
+    const int add = t >= d ? buf[t - d] : 0;
+    __syncthreads();
+    buf[t] += add;
+    __syncthreads();
   }
-  if (threadIdx.x < 2 * kXcds) p.ws.status[8 + threadIdx.x] = 0;   // queue heads of both layers
-  for (int i = threadIdx.x; i < p.n_tiles_n1; i += 256) p.ws.panel_done[i] = 0;
+  const int incl = buf[t], total = buf[255];
   __syncthreads();
-  for (int e = threadIdx.x; e < E; e += 256) {
-    p.ws.counts[e] = cnt[e];
-    p.ws.offsets[e] = off[e];
-    const int kind_full = p.tile_m == 256 ? 2 : (p.tile_m == 128 ? 1 : 0);
-    const int nfull = cnt[e] / p.tile_m;
-    int ti = tbase[e], row = off[e];
-    for (int i = 0; i < nfull; i++, ti++, row += p.tile_m) {
-      p.ws.tile_expert[ti] = e;
-      p.ws.tile_row0[ti] = row;
-      p.ws.tile_rows[ti] = p.tile_m;
-      p.ws.tile_kind[ti] = kind_full;
-    }
-    int h[2] = {0, 0};
-    const int nt = tail_tiles(cnt[e] % p.tile_m, p.tile_m, &h[0], &h[1]);
-    int left = cnt[e] % p.tile_m;
-    for (int i = 0; i < nt; i++, ti++) {
-      const int rows = left < h[i] ? left : h[i];
-      p.ws.tile_expert[ti] = e;
-      p.ws.tile_row0[ti] = row;
-      p.ws.tile_rows[ti] = rows;
-      p.ws.tile_kind[ti] = h[i] == 256 ? 2 : (h[i] == 128 ? 1 : 0);
-      row += rows;
-      left -= rows;
-    }
-  }
-  if (threadIdx.x == 0) p.ws.offsets[E] = off[E];
+  buf[t] = incl - v;
+  __syncthreads();
+  return total;
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 3: stable scatter.  A workgroup owns kIndexChunk consecutive pair ids, cut into runs of 64
+// Step 2: stable scatter.  A workgroup owns kIndexChunk consecutive pair ids, cut into runs of 64
 // (one per wavefront pass); a pair's position is
 //   offsets[e] + rows of e in earlier workgroups + rows of e in earlier runs + rows of e earlier in its run.
+// Every workgroup derives the expert offsets and its own bases from the per-workgroup histograms (a few
+// thousand values at most), which saves a kernel between the histogram and the scatter; workgroup 0 also
+// writes the counts, the offsets, the M-tile table and the zeroed counters of this forward.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
   constexpr int kRuns = kIndexChunk / 64;
   __shared__ int32_t run_cnt[kRuns][kMaxExperts];
+  __shared__ int32_t off[kMaxExperts];     // first row of each expert
+  __shared__ int32_t before[kMaxExperts];  // rows of each expert owned by earlier workgroups
+  __shared__ int32_t tbase[kMaxExperts];   // first M-tile of each expert (workgroup 0)
   const int E = p.s.E, R = p.s.R, k = p.s.k;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int i = threadIdx.x; i < kRuns * kMaxExperts; i += 256) (&run_cnt[0][0])[i] = 0;
+  int my_cnt = 0;
+  {
+    const int e = threadIdx.x;   // E <= 256 = threads
+    int mine = 0;
+    if (e < E) {
+      for (int b = 0; b < p.n_blocks; b++) {
+        const int c = p.ws.block_hist[b * E + e];
+        if (b < (int)blockIdx.x) mine += c;
+        my_cnt += c;
+      }
+    }
+    before[threadIdx.x] = mine;
+  }
+  const int total_rows = exclusive_scan_256(off, my_cnt);
+  if (blockIdx.x == 0) {
+    const int e = threadIdx.x;
+    int h0 = 0, h1 = 0;
+    const int my_tiles = e < E ? my_cnt / p.tile_m + tail_tiles(my_cnt % p.tile_m, p.tile_m, &h0, &h1) : 0;
+    const int n_tiles = exclusive_scan_256(tbase, my_tiles);
+    if (threadIdx.x == 0) {
+      p.ws.status[0] = 0;
+      p.ws.status[1] = n_tiles;
+      p.ws.status[2] = n_tiles * p.n_tiles_n0;
+      p.ws.status[3] = n_tiles * p.n_tiles_n1;
+      p.ws.status[4] = 0;
+      p.ws.offsets[E] = total_rows;
+    }
+    if (threadIdx.x < 2 * kXcds) p.ws.status[8 + threadIdx.x] = 0;   // queue heads of both layers
+    for (int i = threadIdx.x; i < p.n_tiles_n1; i += 256) p.ws.panel_done[i] = 0;
+    if (e < E) {
+      p.ws.counts[e] = my_cnt;
+      p.ws.offsets[e] = off[e];
+      const int kind_full = p.tile_m == 256 ? 2 : (p.tile_m == 128 ? 1 : 0);
+      const int nfull = my_cnt / p.tile_m;
+      int ti = tbase[e], row = off[e];
+      for (int i = 0; i < nfull; i++, ti++, row += p.tile_m) {
+        p.ws.tile_expert[ti] = e;
+        p.ws.tile_row0[ti] = row;
+        p.ws.tile_rows[ti] = p.tile_m;
+        p.ws.tile_kind[ti] = kind_full;
+      }
+      const int h[2] = {h0, h1};
+      const int nt = my_tiles - nfull;
+      int left = my_cnt % p.tile_m;
+      for (int i = 0; i < nt; i++, ti++) {
+        const int rows = left < h[i] ? left : h[i];
+        p.ws.tile_expert[ti] = e;
+        p.ws.tile_row0[ti] = row;
+        p.ws.tile_rows[ti] = rows;
+        p.ws.tile_kind[ti] = h[i] == 256 ? 2 : (h[i] == 128 ? 1 : 0);
+        row += rows;
+        left -= rows;
+      }
+    }
+  }
   __syncthreads();
   int key[kRuns / 4], rank[kRuns / 4];
   const int base = blockIdx.x * kIndexChunk;
@@ -211,7 +224,7 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
     const int q = base + run * 64 + lane;
     const int e = key[s];
     if (e >= 0) {
-      const int pos = p.ws.offsets[e] + p.ws.block_hist[blockIdx.x * E + e] + run_cnt[run][e] + rank[s];
+      const int pos = off[e] + before[e] + run_cnt[run][e] + rank[s];
       p.ws.perm[pos] = q;
       p.ws.inv_perm[q] = pos;
       p.ws.row_token[pos] = q / k;
@@ -220,7 +233,7 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Step 4 (one workgroup): the source segment each M-tile waits for, and the tile schedules.
+// Step 3: the source segment each M-tile waits for, and the tile schedules.
 //
 // A tile can start once all its rows have arrived (Section 2.2.1); its rows are in source order, so that is
 // the segment of its last row.
@@ -236,7 +249,7 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
 // Layer1: per tile height, the M-tiles are dealt to the XCDs in contiguous chunks and every XCD sweeps its chunk
 // column-panel-major, 4 panels at a time (Fig. 6).
 // ---------------------------------------------------------------------------------------------
-constexpr int kTileCap = 4096;  // tiles whose table fits the LDS copies of the schedule builder
+constexpr int kTileCap = 2048;  // tiles whose table fits the LDS copies of the schedule builder
 
 __device__ inline ItemRec make_item(const Workspace& ws, int m, int n) {
   ItemRec r;
@@ -300,7 +313,7 @@ __device__ inline void emit_chunked(const Workspace& ws, ItemRec* items, const O
   }
 }
 
-__global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
+__global__ __launch_bounds__(1024) void k_index_schedule_large(IndexParams p) {
   __shared__ int32_t cls_first[4];  // first position in order[] of the tiles of kind 2, 1, 0, and the end
   __shared__ int32_t key_pos[3 * kMaxSegments];
   __shared__ uint8_t keys[kTileCap];
@@ -405,6 +418,170 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   }
 }
 
+// The schedule builder for tables of up to kTileCap tiles (anything but very large batches): a few workgroups, each
+// of which copies the tile table into LDS, sorts it there (every tile finds its own rank, all in parallel) and
+// then writes its share of the item records.  k_index_schedule_large above is the one-workgroup version without
+// the size limit.
+constexpr int kScheduleWgs = 8;
+
+struct ScheduleLds {
+  int32_t row0[kTileCap];
+  uint16_t rows[kTileCap];
+  uint16_t ord0[kTileCap];   // layer0 order: position -> tile
+  uint16_t ord1[kTileCap];   // layer1 order (height class, then table order)
+  uint8_t expert[kTileCap];
+  uint8_t kind[kTileCap];
+  uint8_t ready[kTileCap];
+  uint8_t key0[kTileCap + 4];   // (height class, segment) or the height class alone; padded with 0xff
+  uint8_t key1[kTileCap + 4];   // height class
+  int16_t run_first[3][kMaxExperts];  // per height class: first and last position of each expert's tiles in ord0
+  int16_t run_last[3][kMaxExperts];
+  int32_t cls_first[4];
+  int32_t cls_count[3];
+  int32_t queue_pos[3][kXcds];
+};
+
+__device__ inline ItemRec make_item_lds(const ScheduleLds& L, int m, int n) {
+  ItemRec r;
+  r.m_tile = m;
+  r.n_tile = n;
+  r.expert = L.expert[m];
+  r.row0 = L.row0[m];
+  r.nrows = L.rows[m];
+  r.kind = L.kind[m];
+  r.ready_seg = L.ready[m];
+  r.pad = 0;
+  return r;
+}
+
+// ord[rank of tile m] = m for the stable order by key (keys < 0xff; the padding never counts).
+__device__ inline void rank_sort(const uint8_t* key, uint16_t* ord, int n, int tid) {
+  const uint32_t* words = (const uint32_t*)key;
+  const int nw = (n + 3) >> 2;
+  for (int m = tid; m < n; m += 1024) {
+    const int km = key[m];
+    int rank = 0;
+    for (int j4 = 0; j4 < nw; j4++) {
+      const uint32_t w = words[j4];
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        const int kj = (w >> (8 * b)) & 0xff, j = j4 * 4 + b;
+        rank += (kj < km || (kj == km && j < m)) ? 1 : 0;
+      }
+    }
+    ord[rank] = (uint16_t)m;
+  }
+}
+
+__global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
+  __shared__ __attribute__((aligned(16))) ScheduleLds L;
+  const int n_tiles = p.ws.status[1];
+  const int tid = threadIdx.x;
+  const int S = p.s.S;
+  const int nseg = p.layer0_order == 1 ? S : 1;
+  if (tid < 3) L.cls_count[tid] = 0;
+  for (int i = tid; i < 3 * kMaxExperts; i += 1024) (&L.run_first[0][0])[i] = -1;
+  __syncthreads();
+  for (int m = tid; m < n_tiles + 4; m += 1024) {
+    if (m >= n_tiles) {
+      L.key0[m] = 0xff;
+      L.key1[m] = 0xff;
+      continue;
+    }
+    const int r0 = p.ws.tile_row0[m], nr = p.ws.tile_rows[m], kd = p.ws.tile_kind[m];
+    const int t = p.ws.row_token[r0 + nr - 1];
+    int s = 0;
+    while (s + 1 < S && p.seg_offsets[s + 1] <= t) s++;
+    L.row0[m] = r0;
+    L.rows[m] = (uint16_t)nr;
+    L.kind[m] = (uint8_t)kd;
+    L.expert[m] = (uint8_t)p.ws.tile_expert[m];
+    L.ready[m] = (uint8_t)s;
+    L.key0[m] = (uint8_t)((2 - kd) * nseg + (nseg > 1 ? s : 0));
+    L.key1[m] = (uint8_t)(2 - kd);
+    atomicAdd(&L.cls_count[2 - kd], 1);
+    if (blockIdx.x == 0) p.ws.tile_ready[m] = s;
+  }
+  __syncthreads();
+  rank_sort(L.key0, L.ord0, n_tiles, tid);
+  if (nseg > 1) rank_sort(L.key1, L.ord1, n_tiles, tid);
+  if (tid == 0) {
+    int pos = 0;
+    for (int c = 0; c < 3; c++) {
+      L.cls_first[c] = pos;
+      pos += L.cls_count[c];
+    }
+    L.cls_first[3] = pos;
+  }
+  // layer1 queues: XCD x gets a contiguous chunk of every height class, tallest first
+  const int cap = (n_tiles + 3 * kXcds) / kXcds * p.n_tiles_n1;   // room per queue
+  if (tid < kXcds) {
+    int pos = tid * cap;
+    for (int c = 0; c < 3; c++) {
+      L.queue_pos[c][tid] = pos;
+      const int nt = L.cls_count[c], chunk = (nt + kXcds - 1) / kXcds;
+      const int cnt = nt == 0 ? 0 : max(0, min(chunk, nt - tid * chunk));
+      pos += cnt * p.n_tiles_n1;
+    }
+    if (blockIdx.x == 0) {
+      const int n0 = n_tiles * p.n_tiles_n0;
+      p.ws.status[24 + tid] = tid < n0 ? (n0 - tid + kXcds - 1) / kXcds : 0;   // layer0: positions tid, tid + 8, ...
+      p.ws.status[32 + tid] = pos - tid * cap;
+      p.ws.status[40 + tid] = tid * cap;
+    }
+  }
+  __syncthreads();
+  const uint16_t* ord1 = nseg > 1 ? L.ord1 : L.ord0;
+  const int gtid = blockIdx.x * 1024 + tid, gthreads = gridDim.x * 1024;
+  if (p.layer0_order == 0) {
+    // where each expert's tiles sit inside a height class (they are contiguous: the sort is stable and the table is
+    // expert-major)
+    for (int i = tid; i < n_tiles; i += 1024) {
+      const int m = L.ord0[i], c = 2 - L.kind[m], e = L.expert[m];
+      const int lo = L.cls_first[c], hi = L.cls_first[c + 1];
+      if (i == lo || L.expert[L.ord0[i - 1]] != e) L.run_first[c][e] = (int16_t)i;
+      if (i == hi - 1 || L.expert[L.ord0[i + 1]] != e) L.run_last[c][e] = (int16_t)i;
+    }
+    __syncthreads();
+    // per height: experts in order; inside an expert groups of 8 column tiles, the expert's M-tiles, the 8 columns
+    const int n_groups = (p.n_tiles_n0 + 7) >> 3;
+    for (int w = gtid; w < n_tiles * n_groups; w += gthreads) {
+      const int i = w / n_groups, g = w % n_groups;
+      const int m = L.ord0[i], c = 2 - L.kind[m], e = L.expert[m];
+      const int lo = L.cls_first[c];
+      const int a = L.run_first[c][e], cnt = L.run_last[c][e] - a + 1;
+      const int gw = min(8, p.n_tiles_n0 - g * 8);
+      const int pos = lo * p.n_tiles_n0 + (a - lo) * p.n_tiles_n0 + g * 8 * cnt + (i - a) * gw;
+      ItemRec r = make_item_lds(L, m, 0);
+      for (int n = 0; n < gw; n++) {
+        r.n_tile = g * 8 + n;
+        p.ws.items0[pos + n] = r;
+      }
+    }
+  } else {
+    for (int i = gtid; i < n_tiles * p.n_tiles_n0; i += gthreads)
+      p.ws.items0[i] = make_item_lds(L, L.ord0[i / p.n_tiles_n0], i % p.n_tiles_n0);
+  }
+  // layer1: every XCD sweeps its chunk of a height class per group of 4 column panels: the chunk's tiles, each with
+  // the 4 panels; panel groups ascend, so all M-tiles of the chunk finish panel group g before g + 1 (Fig. 6)
+  const int n_groups1 = (p.n_tiles_n1 + 3) >> 2;
+  for (int w = gtid; w < n_tiles * n_groups1; w += gthreads) {
+    const int ig = w / n_groups1, g = w % n_groups1;
+    const int m = ord1[ig], c = 2 - L.kind[m];
+    const int i = ig - L.cls_first[c], nt = L.cls_count[c];
+    const int chunk = (nt + kXcds - 1) / kXcds;
+    const int x = i / chunk, j = i % chunk;
+    const int cnt = min(chunk, nt - x * chunk);
+    const int gw = min(4, p.n_tiles_n1 - g * 4);
+    const int pos = L.queue_pos[c][x] + g * 4 * cnt + j * gw;
+    ItemRec r = make_item_lds(L, m, 0);
+    for (int n = 0; n < gw; n++) {
+      r.n_tile = g * 4 + n;
+      p.ws.items1[pos + n] = r;
+    }
+  }
+}
+
 __global__ void k_tile_heights(const int32_t* __restrict__ kind, int32_t* __restrict__ height, int n) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < n) height[i] = 64 << kind[i];
@@ -459,9 +636,11 @@ hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalPa
 hipError_t launch_index_build(const IndexParams& p, hipStream_t st) {
   if (p.s.R == 0) return hipSuccess;
   hipLaunchKernelGGL(k_index_hist, dim3(p.n_blocks), dim3(256), 0, st, p);
-  hipLaunchKernelGGL(k_index_scan, dim3(1), dim3(256), 0, st, p);
   hipLaunchKernelGGL(k_index_scatter, dim3(p.n_blocks), dim3(256), 0, st, p);
-  hipLaunchKernelGGL(k_index_schedule, dim3(1), dim3(1024), 0, st, p);
+  if (p.max_tiles <= kTileCap && p.force_large_schedule == 0)
+    hipLaunchKernelGGL(k_index_schedule, dim3(kScheduleWgs), dim3(1024), 0, st, p);
+  else
+    hipLaunchKernelGGL(k_index_schedule_large, dim3(1), dim3(1024), 0, st, p);
   return hipGetLastError();
 }
 

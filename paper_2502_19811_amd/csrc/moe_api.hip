@@ -27,6 +27,7 @@ struct moe_plan {
   // derived
   int32_t n_index_blocks;
   int32_t max_tiles;
+  int32_t large_schedule;  // 1: always the one-workgroup schedule builder
   int32_t n_tiles_n0, n_tiles_n1;
   size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
       off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_h, off_Y, total_bytes;
@@ -196,6 +197,11 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     p->n_cu = (int32_t)v;
     return MOE_OK;
   }
+  if (!strcmp(key, "large_schedule")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->large_schedule = (int32_t)v;
+    return MOE_OK;
+  }
   if (!strcmp(key, "profile")) {
     if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
     if (v == 1 && !p->ev_created) {
@@ -221,6 +227,7 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   else if (!strcmp(key, "phases")) *v = p->phases;
   else if (!strcmp(key, "n_cu")) *v = p->n_cu;
   else if (!strcmp(key, "profile")) *v = p->profile;
+  else if (!strcmp(key, "large_schedule")) *v = p->large_schedule;
   else return MOE_ERR_INVALID_ARG;
   return MOE_OK;
 }
@@ -275,6 +282,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     ip.n_tiles_n1 = p->n_tiles_n1;
     ip.layer0_order = p->layer0_order;
     ip.layer1_order = p->layer1_order;
+    ip.max_tiles = p->max_tiles;
+    ip.force_large_schedule = p->large_schedule;
     memcpy(ip.seg_offsets, p->seg_offsets, sizeof(int32_t) * (s.S + 1));
     if (launch_index_build(ip, st) != hipSuccess) return MOE_ERR_HIP;
   }

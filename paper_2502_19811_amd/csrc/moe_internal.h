@@ -34,7 +34,7 @@ struct Workspace {
   int32_t* perm;          // [R] sorted row -> pair id
   int32_t* inv_perm;      // [R] pair id -> sorted row
   int32_t* row_token;     // [R] sorted row -> token (row of x to gather)
-  int32_t* block_hist;    // [n_index_blocks * E] per-block counts, then per-block bases
+  int32_t* block_hist;    // [n_index_blocks * E] rows of each expert among a workgroup's pair ids
   int32_t* tile_expert;   // [max_tiles]
   int32_t* tile_row0;     // [max_tiles]
   int32_t* tile_rows;     // [max_tiles]
@@ -61,6 +61,8 @@ struct IndexParams {
   int32_t tile_m;
   int32_t n_tiles_n0, n_tiles_n1;
   int32_t layer0_order, layer1_order;
+  int32_t max_tiles;             // bound on the M-tiles of this plan
+  int32_t force_large_schedule;  // 1: build the schedules with the one-workgroup kernel whatever the size
   int32_t seg_offsets[kMaxSegments + 1];
 };
 
