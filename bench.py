@@ -131,7 +131,10 @@ def main() -> int:
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},
         "phases_us": {"index_build": round(phase_ms[0] * 1e3, 1), "layer0_gemm": round(phase_ms[1] * 1e3, 1),
                       "layer1_gemm_combine": round(phase_ms[2] * 1e3, 1), "combine_alone": round(phase_ms[3] * 1e3, 1),
-                      "forwards_averaged": n_prof, "layer1_tflops": round(l1_tflops, 1)},
+                      "forwards_averaged": n_prof, "layer1_tflops": round(l1_tflops, 1),
+                      # the reduction reads k rows of Y per token (plus 8 index/weight bytes per row) and writes out
+                      "combine_hbm_gbps": round((2.0 * cfg.R * cfg.H + 8.0 * cfg.R + 2.0 * cfg.T * cfg.H)
+                                                / (phase_ms[3] * 1e-3) / 1e9, 1) if phase_ms[3] > 0 else None},
         "roofline": {"bound": "mfma", "kernel": "k_group_gemm layer0 (fc1 + activation)", "achieved": round(l0_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(l0_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": traffic},
