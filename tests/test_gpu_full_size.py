@@ -23,7 +23,7 @@ def _sample_tokens(cfg, offsets, perm, tiles, n_random=48):
     return np.array(sorted(toks), dtype=np.int64)
 
 
-@pytest.mark.parametrize("name", ["mixtral", "qwen2", "phi35", "skewed"])
+@pytest.mark.parametrize("name", ["mixtral", "qwen2", "phi35", "skewed", "qwen2_table2", "mixtral_tp8"])
 def test_full_size_sampled_parity(name):
     import gpu_harness as H
     cfg = wl.CONFIGS[name]
@@ -52,3 +52,25 @@ def test_full_size_sampled_parity(name):
     # nothing outside the sample is garbage: finite everywhere, and of the sample's magnitude
     assert np.isfinite(run.out).all()
     assert 0.5 < run.out.std() / ref.std() < 2.0
+
+
+@pytest.mark.parametrize("name", ["mixtral", "qwen2_table2"])
+def test_full_size_token_reversal_moves_every_row_bit_for_bit(name):
+    """Every output row is the same sum in the same order wherever its token sits: reversing the token order reverses
+    the output rows exactly.  This checks every row of the full-size output, not a sample, against a run in which
+    each routed row lands in a different tile and a different position of it."""
+    import gpu_harness as H
+    cfg = wl.CONFIGS[name]
+    print(f"token reversal {name}: generating inputs", flush=True)
+    inp = wl.make_inputs(cfg, threads=16)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    layer = H.GpuLayer(cfg, inp, ids, w)
+    layer.forward(); base = layer.results(); layer.close()
+    assert base.status == 0
+    rev = wl.MoEInputs(cfg, np.ascontiguousarray(inp.x[::-1]), inp.W1, inp.W2, np.ascontiguousarray(inp.logits[::-1]),
+                       inp.seg_offsets)
+    print("  reversed forward", flush=True)
+    l2 = H.GpuLayer(cfg, rev, np.ascontiguousarray(ids[::-1]), np.ascontiguousarray(w[::-1]))
+    l2.forward(); r2 = l2.results(); l2.close()
+    assert r2.status == 0
+    np.testing.assert_array_equal(r2.out[::-1], base.out)
