@@ -28,6 +28,11 @@ SMALL_CASES = [
     _case("one_expert", T=70, H=256, F=256, E=1, k=1, act=wl.ACT_GELU, S=1, seed=103),
     _case("single_token", T=1, H=256, F=256, E=4, k=2, act=wl.ACT_SWIGLU, S=2, seed=104),
     _case("wide_rows", T=700, H=768, F=640, E=3, k=3, act=wl.ACT_SWIGLU, S=8, seed=105),
+    # the limits of the interface at once: 256 experts, 16 experts per token, 64 source segments
+    _case("max_limits", T=96, H=256, F=128, E=256, k=16, act=wl.ACT_SWIGLU, S=64, seed=106),
+    # GELU on full-height tiles (several per expert, ragged tail), and a second full-height SwiGLU case with k = 1
+    _case("gelu_tall", T=1100, H=512, F=512, E=2, k=1, act=wl.ACT_GELU, S=4, seed=107),
+    _case("swiglu_tall", T=900, H=256, F=256, E=2, k=1, act=wl.ACT_SWIGLU, S=3, seed=108),
 ]
 
 
