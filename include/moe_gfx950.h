@@ -78,8 +78,8 @@ int moe_plan_destroy(moe_plan_t *plan);
  *   "profile"      1: every forward records HIP events on its stream before and after each phase
  *                  (this call then creates the events; read them with moe_plan_phase_times)
  *   "large_schedule" 1: build the tile schedules with the one-workgroup kernel that has no limit on the
- *                  number of M-tiles (the default picks it only above 2048 tiles; the schedules are
- *                  the same either way)
+ *                  number of M-tiles (the default picks it only above 2048 tiles); its orders are simpler
+ *                  (less operand sharing inside an XCD), the results are the same bit for bit
  * Unknown key or out-of-range value: MOE_ERR_INVALID_ARG. */
 int moe_plan_set_option(moe_plan_t *plan, const char *key, int64_t value);
 int moe_plan_get_option(const moe_plan_t *plan, const char *key, int64_t *value);

@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
 // Layer1: per tile height, the M-tiles are dealt to the XCDs in contiguous chunks and every XCD sweeps its chunk
 // column-panel-major, 4 panels at a time (Fig. 6).
 // ---------------------------------------------------------------------------------------------
-constexpr int kTileCap = 2048;  // tiles whose table fits the LDS copies of the schedule builder
+constexpr int kTileCap = kScheduleTileCap;  // tiles whose table fits the LDS copies of the schedule builder
 
 __device__ inline ItemRec make_item(const Workspace& ws, int m, int n) {
   ItemRec r;
@@ -421,24 +421,36 @@ __global__ __launch_bounds__(1024) void k_index_schedule_large(IndexParams p) {
 // The schedule builder for tables of up to kTileCap tiles (anything but very large batches): a few workgroups, each
 // of which copies the tile table into LDS, sorts it there (every tile finds its own rank, all in parallel) and
 // then writes its share of the item records.  k_index_schedule_large above is the one-workgroup version without
-// the size limit.
+// the size limit (and with simpler orders).
+//
+// Locality order (layer0 with order 0, layer1 with the separate combine kernel): per tile height, an expert's
+// M-tiles are cut into blocks of up to 8; block b goes to XCD b % 8, whose queue holds its blocks one after the
+// other, tallest first.  Inside a block of G M-tiles the column tiles ascend and the block's M-tiles are the inner
+// loop.  The 32 workgroups of an XCD, taking consecutive items, then work on G M-tiles x about 32/G column tiles of
+// one expert wherever in the block they are, and share both operands in their L2; an expert with few rows is
+// streamed through one XCD only (its weight panels are fetched once).
 constexpr int kScheduleWgs = 8;
 
 struct ScheduleLds {
   int32_t row0[kTileCap];
+  int32_t blk_off[kTileCap];   // M-tiles ahead of block b in its XCD's queue
   uint16_t rows[kTileCap];
-  uint16_t ord0[kTileCap];   // layer0 order: position -> tile
-  uint16_t ord1[kTileCap];   // layer1 order (height class, then table order)
+  uint16_t ord0[kTileCap];     // layer0 order: position -> tile
+  uint16_t ord1[kTileCap];     // layer1 order (height class, then table order)
+  uint16_t blk_g[kTileCap];    // M-tiles of block b
   uint8_t expert[kTileCap];
   uint8_t kind[kTileCap];
   uint8_t ready[kTileCap];
   uint8_t key0[kTileCap + 4];   // (height class, segment) or the height class alone; padded with 0xff
   uint8_t key1[kTileCap + 4];   // height class
-  int16_t run_first[3][kMaxExperts];  // per height class: first and last position of each expert's tiles in ord0
+  int16_t run_first[3][kMaxExperts];  // per height class: first and last position of each expert's tiles in ord1
   int16_t run_last[3][kMaxExperts];
+  int32_t blk_base[1024];             // [3][kMaxExperts] flattened (+ padding): first block of (class, expert)
   int32_t cls_first[4];
   int32_t cls_count[3];
   int32_t queue_pos[3][kXcds];
+  int32_t q_len_t[kXcds], q_base_t[kXcds];   // locality order: M-tiles per XCD queue, and ahead of it
+  int32_t n_blocks;
 };
 
 __device__ inline ItemRec make_item_lds(const ScheduleLds& L, int m, int n) {
@@ -473,13 +485,28 @@ __device__ inline void rank_sort(const uint8_t* key, uint16_t* ord, int n, int t
   }
 }
 
+// Items of one layer in the locality order (see above); n_tiles_n column tiles.
+__device__ inline void emit_blocks(const ScheduleLds& L, const uint16_t* ord, ItemRec* items, int n_tiles, int n_tiles_n,
+                                   int gtid, int gthreads) {
+  for (int w = gtid; w < n_tiles * n_tiles_n; w += gthreads) {
+    const int i = w / n_tiles_n, n = w % n_tiles_n;
+    const int m = ord[i], c = 2 - L.kind[m], e = L.expert[m];
+    const int j = i - L.run_first[c][e];
+    const int b = L.blk_base[c * kMaxExperts + e] + (j >> 3), g = L.blk_g[b], jm = j & 7;
+    const int pos = (L.q_base_t[b & (kXcds - 1)] + L.blk_off[b]) * n_tiles_n + n * g + jm;
+    items[pos] = make_item_lds(L, m, n);
+  }
+}
+
 __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   __shared__ __attribute__((aligned(16))) ScheduleLds L;
   const int n_tiles = p.ws.status[1];
   const int tid = threadIdx.x;
   const int S = p.s.S;
   const int nseg = p.layer0_order == 1 ? S : 1;
+  const bool local0 = p.layer0_order == 0, local1 = p.layer1_order == 0;
   if (tid < 3) L.cls_count[tid] = 0;
+  if (tid < kXcds) L.q_len_t[tid] = 0;
   for (int i = tid; i < 3 * kMaxExperts; i += 1024) (&L.run_first[0][0])[i] = -1;
   __syncthreads();
   for (int m = tid; m < n_tiles + 4; m += 1024) {
@@ -513,7 +540,7 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
     }
     L.cls_first[3] = pos;
   }
-  // layer1 queues: XCD x gets a contiguous chunk of every height class, tallest first
+  // layer1 in panel-major order (in-kernel combine): XCD x gets a contiguous chunk of every height class
   const int cap = (n_tiles + 3 * kXcds) / kXcds * p.n_tiles_n1;   // room per queue
   if (tid < kXcds) {
     int pos = tid * cap;
@@ -523,61 +550,107 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
       const int cnt = nt == 0 ? 0 : max(0, min(chunk, nt - tid * chunk));
       pos += cnt * p.n_tiles_n1;
     }
-    if (blockIdx.x == 0) {
-      const int n0 = n_tiles * p.n_tiles_n0;
-      p.ws.status[24 + tid] = tid < n0 ? (n0 - tid + kXcds - 1) / kXcds : 0;   // layer0: positions tid, tid + 8, ...
+    if (blockIdx.x == 0 && !local1) {
       p.ws.status[32 + tid] = pos - tid * cap;
       p.ws.status[40 + tid] = tid * cap;
     }
+    if (blockIdx.x == 0 && !local0) {
+      const int n0 = n_tiles * p.n_tiles_n0;
+      p.ws.status[24 + tid] = tid < n0 ? (n0 - tid + kXcds - 1) / kXcds : 0;   // positions tid, tid + 8, ...
+    }
   }
   __syncthreads();
-  const uint16_t* ord1 = nseg > 1 ? L.ord1 : L.ord0;
+  const uint16_t* ord1 = nseg > 1 ? L.ord1 : L.ord0;   // height class, then table order (expert-major)
   const int gtid = blockIdx.x * 1024 + tid, gthreads = gridDim.x * 1024;
-  if (p.layer0_order == 0) {
+  if (local0 || local1) {
     // where each expert's tiles sit inside a height class (they are contiguous: the sort is stable and the table is
-    // expert-major)
+    // expert-major), the blocks they are cut into, and the XCD queues the blocks go to
     for (int i = tid; i < n_tiles; i += 1024) {
-      const int m = L.ord0[i], c = 2 - L.kind[m], e = L.expert[m];
+      const int m = ord1[i], c = 2 - L.kind[m], e = L.expert[m];
       const int lo = L.cls_first[c], hi = L.cls_first[c + 1];
-      if (i == lo || L.expert[L.ord0[i - 1]] != e) L.run_first[c][e] = (int16_t)i;
-      if (i == hi - 1 || L.expert[L.ord0[i + 1]] != e) L.run_last[c][e] = (int16_t)i;
+      if (i == lo || L.expert[ord1[i - 1]] != e) L.run_first[c][e] = (int16_t)i;
+      if (i == hi - 1 || L.expert[ord1[i + 1]] != e) L.run_last[c][e] = (int16_t)i;
     }
     __syncthreads();
-    // per height: experts in order; inside an expert groups of 8 column tiles, the expert's M-tiles, the 8 columns
-    const int n_groups = (p.n_tiles_n0 + 7) >> 3;
-    for (int w = gtid; w < n_tiles * n_groups; w += gthreads) {
-      const int i = w / n_groups, g = w % n_groups;
-      const int m = L.ord0[i], c = 2 - L.kind[m], e = L.expert[m];
-      const int lo = L.cls_first[c];
-      const int a = L.run_first[c][e], cnt = L.run_last[c][e] - a + 1;
-      const int gw = min(8, p.n_tiles_n0 - g * 8);
-      const int pos = lo * p.n_tiles_n0 + (a - lo) * p.n_tiles_n0 + g * 8 * cnt + (i - a) * gw;
-      ItemRec r = make_item_lds(L, m, 0);
-      for (int n = 0; n < gw; n++) {
-        r.n_tile = g * 8 + n;
-        p.ws.items0[pos + n] = r;
+    {
+      // blocks per (class, expert), then an exclusive prefix sum over the 768 pairs (1024 threads, one each)
+      const int c = tid / kMaxExperts, e = tid % kMaxExperts;
+      int nb = 0;
+      if (c < 3 && L.run_first[c][e] >= 0) nb = (L.run_last[c][e] - L.run_first[c][e] + 1 + 7) >> 3;
+      L.blk_base[tid] = nb;
+      __syncthreads();
+      for (int d = 1; d < 1024; d <<= 1) {
+        const int add = tid >= d ? L.blk_base[tid - d] : 0;
+        __syncthreads();
+        L.blk_base[tid] += add;
+        __syncthreads();
+      }
+      const int incl = L.blk_base[tid];
+      if (tid == 1023) L.n_blocks = incl;
+      __syncthreads();
+      L.blk_base[tid] = incl - nb;
+      __syncthreads();
+    }
+    for (int i = tid; i < n_tiles; i += 1024) {
+      const int m = ord1[i], c = 2 - L.kind[m], e = L.expert[m];
+      const int j = i - L.run_first[c][e], cnt = L.run_last[c][e] - L.run_first[c][e] + 1;
+      if ((j & 7) == 0) L.blk_g[L.blk_base[c * kMaxExperts + e] + (j >> 3)] = (uint16_t)min(8, cnt - j);
+    }
+    __syncthreads();
+    const int n_blocks = L.n_blocks;
+    for (int b = tid; b < n_blocks; b += 1024) {
+      int off = 0;
+      for (int q = b - kXcds; q >= 0; q -= kXcds) off += L.blk_g[q];
+      L.blk_off[b] = off;
+      if (b + kXcds >= n_blocks) L.q_len_t[b & (kXcds - 1)] = off + L.blk_g[b];
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int pos = 0;
+      for (int x = 0; x < kXcds; x++) {
+        L.q_base_t[x] = pos;
+        pos += L.q_len_t[x];
       }
     }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < kXcds) {
+      if (local0) {
+        p.ws.status[24 + tid] = L.q_len_t[tid] * p.n_tiles_n0;
+        p.ws.status[48 + tid] = L.q_base_t[tid] * p.n_tiles_n0;
+      }
+      if (local1) {
+        p.ws.status[32 + tid] = L.q_len_t[tid] * p.n_tiles_n1;
+        p.ws.status[40 + tid] = L.q_base_t[tid] * p.n_tiles_n1;
+      }
+    }
+  }
+  if (local0) {
+    emit_blocks(L, ord1, p.ws.items0, n_tiles, p.n_tiles_n0, gtid, gthreads);
   } else {
+    // by source segment (Fig. 5): all column tiles of an M-tile in a row; list position i belongs to XCD i % 8
     for (int i = gtid; i < n_tiles * p.n_tiles_n0; i += gthreads)
       p.ws.items0[i] = make_item_lds(L, L.ord0[i / p.n_tiles_n0], i % p.n_tiles_n0);
   }
-  // layer1: every XCD sweeps its chunk of a height class per group of 4 column panels: the chunk's tiles, each with
-  // the 4 panels; panel groups ascend, so all M-tiles of the chunk finish panel group g before g + 1 (Fig. 6)
-  const int n_groups1 = (p.n_tiles_n1 + 3) >> 2;
-  for (int w = gtid; w < n_tiles * n_groups1; w += gthreads) {
-    const int ig = w / n_groups1, g = w % n_groups1;
-    const int m = ord1[ig], c = 2 - L.kind[m];
-    const int i = ig - L.cls_first[c], nt = L.cls_count[c];
-    const int chunk = (nt + kXcds - 1) / kXcds;
-    const int x = i / chunk, j = i % chunk;
-    const int cnt = min(chunk, nt - x * chunk);
-    const int gw = min(4, p.n_tiles_n1 - g * 4);
-    const int pos = L.queue_pos[c][x] + g * 4 * cnt + j * gw;
-    ItemRec r = make_item_lds(L, m, 0);
-    for (int n = 0; n < gw; n++) {
-      r.n_tile = g * 4 + n;
-      p.ws.items1[pos + n] = r;
+  if (local1) {
+    emit_blocks(L, ord1, p.ws.items1, n_tiles, p.n_tiles_n1, gtid, gthreads);
+  } else {
+    // panel-major (Fig. 6): every XCD sweeps its chunk of a height class per group of 4 column panels: the chunk's
+    // tiles, each with the 4 panels; panel groups ascend, so all M-tiles of the chunk finish group g before g + 1
+    const int n_groups1 = (p.n_tiles_n1 + 3) >> 2;
+    for (int w = gtid; w < n_tiles * n_groups1; w += gthreads) {
+      const int ig = w / n_groups1, g = w % n_groups1;
+      const int m = ord1[ig], c = 2 - L.kind[m];
+      const int i = ig - L.cls_first[c], nt = L.cls_count[c];
+      const int chunk = (nt + kXcds - 1) / kXcds;
+      const int x = i / chunk, j = i % chunk;
+      const int cnt = min(chunk, nt - x * chunk);
+      const int gw = min(4, p.n_tiles_n1 - g * 4);
+      const int pos = L.queue_pos[c][x] + g * 4 * cnt + j * gw;
+      ItemRec r = make_item_lds(L, m, 0);
+      for (int n = 0; n < gw; n++) {
+        r.n_tile = g * 4 + n;
+        p.ws.items1[pos + n] = r;
+      }
     }
   }
 }
@@ -637,7 +710,7 @@ hipError_t launch_index_build(const IndexParams& p, hipStream_t st) {
   if (p.s.R == 0) return hipSuccess;
   hipLaunchKernelGGL(k_index_hist, dim3(p.n_blocks), dim3(256), 0, st, p);
   hipLaunchKernelGGL(k_index_scatter, dim3(p.n_blocks), dim3(256), 0, st, p);
-  if (p.max_tiles <= kTileCap && p.force_large_schedule == 0)
+  if (!uses_large_schedule(p.max_tiles, p.force_large_schedule))
     hipLaunchKernelGGL(k_index_schedule, dim3(kScheduleWgs), dim3(1024), 0, st, p);
   else
     hipLaunchKernelGGL(k_index_schedule_large, dim3(1), dim3(1024), 0, st, p);

@@ -323,8 +323,13 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     a.n_mfma = p->n_cu;
     a.queue_heads = ws.status + 8;
     a.queue_len = ws.status + 24;
-    a.queue_base = nullptr;
-    a.queue_stride = kXcds;
+    if (p->layer0_order == 0 && !uses_large_schedule(p->max_tiles, p->large_schedule)) {
+      a.queue_base = ws.status + 48;   // contiguous per-XCD queues (locality order)
+      a.queue_stride = 1;
+    } else {
+      a.queue_base = nullptr;          // queue x = list positions x, x + 8, ...
+      a.queue_stride = kXcds;
+    }
     if (launch_layer0(a, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
   }
 

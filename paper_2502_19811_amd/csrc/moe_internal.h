@@ -16,6 +16,10 @@ constexpr int kTileK = 32;          // depth of one LDS stage
 constexpr int kStages = 4;          // LDS stages in flight
 constexpr int kCombineChunk = 256;  // tokens per unit of combine work
 constexpr int kXcds = 8;            // XCDs of the device: workgroup i runs on XCD i % 8
+constexpr int kScheduleTileCap = 2048;  // M-tiles up to which the multi-workgroup schedule builder is used
+
+// Which schedule builder a plan uses: the one-workgroup kernel has no size limit (and simpler orders).
+inline bool uses_large_schedule(int max_tiles, int force) { return force != 0 || max_tiles > kScheduleTileCap; }
 
 // Item of a GroupGEMM schedule: one (M-tile, column tile) pair with the M-tile's table row copied in, so that a
 // workgroup needs a single 32-byte read to start on it.
@@ -28,7 +32,8 @@ struct Workspace {
   int32_t* status;        // [64]  0: device status word, 1: n_tiles, 2: items of layer0, 3: items of layer1,
                           //       4: combine unit counter; per XCD: 8..15 layer0 queue heads, 16..23 layer1 queue
                           //       heads, 24..31 layer0 queue lengths, 32..39 layer1 queue lengths, 40..47 layer1
-                          //       queue bases (layer0: queue x is list positions x, x+8, ...)
+                          //       queue bases, 48..55 layer0 queue bases (only with contiguous layer0 queues;
+                          //       otherwise layer0's queue x is list positions x, x+8, ...)
   int32_t* counts;        // [E]
   int32_t* offsets;       // [E+1]
   int32_t* perm;          // [R] sorted row -> pair id
