@@ -631,13 +631,30 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     }
     {
       const int c = lane_e % NC;
-#pragma unroll
-      for (int it = 0; it < 32 * NC / 64; it++) {
+      constexpr int NST = 32 * NC / 64;   // 16-byte stores per lane and 32-row block
+      auto staged = [&](int it) {
         const int r = it * (64 / NC) + lane_e / NC;
-        const u32x4 v = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
+        return *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
             cbase + r * RB + ((c ^ ((r / RPB) & (NC - 1))) << 4));
-        const int grow = wm * (MT * 32) + mt * 32 + r;
-        if (grow < nrows) *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v;
+      };
+      if (nrows == BM) {
+        // a full tile (the usual case): all staged chunks are read back first, then stored, so that the stores
+        // do not each wait for an LDS round trip of their own
+        u32x4 v[NST];
+#pragma unroll
+        for (int it = 0; it < NST; it++) v[it] = staged(it);
+#pragma unroll
+        for (int it = 0; it < NST; it++) {
+          const int grow = wm * (MT * 32) + mt * 32 + it * (64 / NC) + lane_e / NC;
+          *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v[it];
+        }
+      } else {
+#pragma unroll
+        for (int it = 0; it < NST; it++) {
+          const u32x4 v = staged(it);
+          const int grow = wm * (MT * 32) + mt * 32 + it * (64 / NC) + lane_e / NC;
+          if (grow < nrows) *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v;
+        }
       }
     }
     if constexpr (kCanPre) {
