@@ -130,7 +130,7 @@ def main() -> int:
                    "layer1_order": moe.moe_plan_get_option(plan, "layer1_order"),
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},
         "phases_us": {"index_build": round(phase_ms[0] * 1e3, 1), "layer0_gemm": round(phase_ms[1] * 1e3, 1),
-                      "layer1_gemm_combine": round(phase_ms[2] * 1e3, 1), "combine_alone": round(phase_ms[3] * 1e3, 1),
+                      "layer1_gemm": round(phase_ms[2] * 1e3, 1), "combine": round(phase_ms[3] * 1e3, 1),
                       "forwards_averaged": n_prof, "layer1_tflops": round(l1_tflops, 1),
                       # the reduction reads k rows of Y per token (plus 8 index/weight bytes per row) and writes out
                       "combine_hbm_gbps": round((2.0 * cfg.R * cfg.H + 8.0 * cfg.R + 2.0 * cfg.T * cfg.H)
