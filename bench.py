@@ -88,6 +88,7 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_forward_us = sorted(v * 1e3 for v in moe.moe_plan_forward_times(plan))
     phase_ms, n_prof = moe.moe_plan_phase_times(plan)
     moe.moe_plan_set_option(plan, "profile", 0)
     status = moe.moe_last_device_status(plan, ws)
@@ -119,6 +120,10 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4),
         "us_per_layer": round(ms_per_step * 1e3, 1),
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        # per forward, from the events the library records on the stream (at most the last 64 forwards)
+        "us_per_layer_min_median_p90": [round(per_forward_us[0], 1), round(per_forward_us[len(per_forward_us) // 2], 1),
+                                        round(per_forward_us[min(len(per_forward_us) - 1, int(0.9 * len(per_forward_us)))], 1)]
+        if per_forward_us else None,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

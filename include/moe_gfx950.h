@@ -148,6 +148,11 @@ int moe_play_arrival(const moe_plan_t *plan, const void *staging, void *x, uint3
  * "profile" option.  ms: host [4]; n_steps: host [1].  Waits for the recorded forwards to finish. */
 int moe_plan_phase_times(moe_plan_t *plan, float *ms, int32_t *n_steps);
 
+/* Time in ms of each forward recorded since the last moe_plan_phase_times call (first event to last event of
+ * the forward; at most 64, at most capacity), for medians and percentiles.  ms: host [capacity]; n_steps: host
+ * [1].  Does not reset the recording; waits for the recorded forwards to finish. */
+int moe_plan_forward_times(moe_plan_t *plan, float *ms, int32_t capacity, int32_t *n_steps);
+
 /* Status word written by the kernels of the last forward (0, or MOE_ERR_TIMEOUT when a bounded
  * flag wait expired).  Synchronises the stream. */
 int moe_last_device_status(const moe_plan_t *plan, const void *workspace, void *hip_stream);

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     moe_plan_destroy,
     moe_plan_get_option,
     moe_plan_max_tiles,
+    moe_plan_forward_times,
     moe_plan_phase_times,
     moe_plan_set_option,
     moe_plan_workspace_bytes,

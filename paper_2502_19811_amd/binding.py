@@ -19,7 +19,7 @@ EXPORTS = [
     "moe_plan_create", "moe_plan_destroy", "moe_plan_set_option", "moe_plan_get_option",
     "moe_plan_workspace_bytes", "moe_plan_max_tiles", "moe_receive_buffer_bytes", "moe_route_topk",
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
-    "moe_status_string", "moe_plan_phase_times", "moe_play_arrival",
+    "moe_status_string", "moe_plan_phase_times", "moe_plan_forward_times", "moe_play_arrival",
 ]
 
 
@@ -76,6 +76,8 @@ def load_library():
     lib.moe_last_device_status.restype = C.c_int
     lib.moe_plan_phase_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.moe_plan_phase_times.restype = C.c_int
+    lib.moe_plan_forward_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
+    lib.moe_plan_forward_times.restype = C.c_int
     lib.moe_play_arrival.argtypes = [C.c_void_p, vp, vp, u32p, u32p, C.c_uint32, C.c_double, C.c_int32, vp]
     lib.moe_play_arrival.restype = C.c_int
     lib.moe_status_string.argtypes = [C.c_int]
@@ -184,3 +186,11 @@ def moe_play_arrival(plan: int, staging, x, seg_ready, seg_counters, ready_epoch
     _check(load_library().moe_play_arrival(plan, _ptr(staging), _ptr(x), _ptr(seg_ready), _ptr(seg_counters),
                                            ready_epoch, float(gbytes_per_s), n_workgroups, _stream(stream)),
            "moe_play_arrival")
+
+
+def moe_plan_forward_times(plan: int, capacity: int = 64):
+    """ms of each forward recorded since the last moe_plan_phase_times call (needs the "profile" option)."""
+    ms = (C.c_float * capacity)()
+    n = C.c_int32()
+    _check(load_library().moe_plan_forward_times(plan, ms, capacity, C.byref(n)), "moe_plan_forward_times")
+    return [float(ms[i]) for i in range(n.value)]

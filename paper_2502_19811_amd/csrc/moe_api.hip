@@ -400,6 +400,18 @@ int moe_plan_phase_times(moe_plan_t* p, float* ms, int32_t* n_steps) {
   return MOE_OK;
 }
 
+int moe_plan_forward_times(moe_plan_t* p, float* ms, int32_t capacity, int32_t* n_steps) {
+  if (!p || !ms || !n_steps || capacity < 0) return MOE_ERR_INVALID_ARG;
+  int n = p->prof_steps < kProfSlots ? p->prof_steps : kProfSlots;
+  if (n > capacity) n = capacity;
+  *n_steps = n;
+  for (int i = 0; i < n; i++) {
+    if (hipEventSynchronize(p->ev[i][4]) != hipSuccess) return MOE_ERR_HIP;
+    if (hipEventElapsedTime(&ms[i], p->ev[i][0], p->ev[i][4]) != hipSuccess) return MOE_ERR_HIP;
+  }
+  return MOE_OK;
+}
+
 int moe_get_index_outputs(const moe_plan_t* p, const void* workspace, int32_t* expert_counts, int32_t* expert_offsets,
                           int32_t* perm, int32_t* inv_perm, void* hip_stream) {
   if (!p || !workspace) return MOE_ERR_INVALID_ARG;
