@@ -41,10 +41,11 @@ def test_plan_create_and_options():
     assert moe.moe_plan_workspace_bytes(plan) > 256 * (512 + 256) * 2           # holds h [R,F] and Y [R,H], R = 256
     assert moe.moe_plan_get_option(plan, "tile_m") in (64, 128, 256)
     for key, val in [("tile_m", 128), ("n_dm", 7), ("layer0_order", 1), ("layer1_order", 0), ("spin_limit", 1000),
-                     ("phases", 3), ("n_cu", 64)]:
+                     ("phases", 3), ("n_cu", 64), ("large_schedule", 1)]:
         moe.moe_plan_set_option(plan, key, val)
         assert moe.moe_plan_get_option(plan, key) == val
-    for key, val in [("tile_m", 100), ("n_dm", -2), ("layer0_order", 2), ("phases", 16), ("no_such_key", 1)]:
+    for key, val in [("tile_m", 100), ("n_dm", -2), ("layer0_order", 2), ("phases", 16), ("large_schedule", 2),
+                     ("no_such_key", 1)]:
         with pytest.raises(moe.MoEError) as e:
             moe.moe_plan_set_option(plan, key, val)
         assert e.value.status == -1
@@ -82,6 +83,26 @@ def test_forward_argument_checks_happen_before_any_gpu_work():
     bad = list(args); bad[8] = addr + 16
     assert lib.moe_layer_forward(*bad) == -1          # workspace not 256-byte aligned
     moe.moe_plan_destroy(plan)
+
+
+def test_timing_calls_without_recorded_forwards():
+    plan = _create()
+    assert moe.moe_plan_forward_times(plan) == []
+    ms, n = moe.moe_plan_phase_times(plan)
+    assert n == 0 and ms == [0.0] * 4
+    lib = moe.load_library()
+    assert lib.moe_plan_forward_times(plan, None, 4, None) == -1
+    moe.moe_plan_destroy(plan)
+
+
+def test_workspace_grows_with_the_batch_and_holds_both_intermediates():
+    sizes = []
+    for T in (128, 256, 1024):
+        plan = _create(T=T, seg_offsets=[T * i // 8 for i in range(9)])
+        sizes.append(moe.moe_plan_workspace_bytes(plan))
+        assert sizes[-1] >= 2 * T * (512 + 256) * 2      # h [R,F] and Y [R,H] in bf16, R = 2T
+        moe.moe_plan_destroy(plan)
+    assert sizes == sorted(sizes) and len(set(sizes)) == 3
 
 
 def test_receive_buffer_bytes_table3():
