@@ -33,6 +33,8 @@ SMALL_CASES = [
     # GELU on full-height tiles (several per expert, ragged tail), and a second full-height SwiGLU case with k = 1
     _case("gelu_tall", T=1100, H=512, F=512, E=2, k=1, act=wl.ACT_GELU, S=4, seed=107),
     _case("swiglu_tall", T=900, H=256, F=256, E=2, k=1, act=wl.ACT_SWIGLU, S=3, seed=108),
+    # more than 2048 M-tiles at tile_m = 64: the one-workgroup schedule builder is chosen by size
+    _case("many_tiles", T=70000, H=256, F=128, E=4, k=2, act=wl.ACT_SWIGLU, S=8, seed=109),
 ]
 
 
