@@ -130,12 +130,27 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
   __shared__ int32_t tbase[kMaxExperts];   // first M-tile of each expert (workgroup 0)
   const int E = p.s.E, R = p.s.R, k = p.s.k;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x; i < kRuns * kMaxExperts; i += 256) (&run_cnt[0][0])[i] = 0;
   int my_cnt = 0;
   {
     const int e = threadIdx.x;   // E <= 256 = threads
     int mine = 0;
-    if (e < E) {
+    constexpr int kHistLds = kRuns * kMaxExperts;   // run_cnt doubles as the landing area of the histograms
+    const int n_hist = p.n_blocks * E;
+    if (n_hist <= kHistLds) {
+      // all histograms in one coalesced sweep, then summed out of LDS (a per-thread walk over the workgroups would
+      // be a chain of dependent global loads)
+      int32_t* hist = &run_cnt[0][0];
+      for (int i = threadIdx.x; i < n_hist; i += 256) hist[i] = p.ws.block_hist[i];
+      __syncthreads();
+      if (e < E) {
+        for (int b = 0; b < p.n_blocks; b++) {
+          const int c = hist[b * E + e];
+          if (b < (int)blockIdx.x) mine += c;
+          my_cnt += c;
+        }
+      }
+      __syncthreads();
+    } else if (e < E) {
       for (int b = 0; b < p.n_blocks; b++) {
         const int c = p.ws.block_hist[b * E + e];
         if (b < (int)blockIdx.x) mine += c;
@@ -144,6 +159,7 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
     }
     before[threadIdx.x] = mine;
   }
+  for (int i = threadIdx.x; i < kRuns * kMaxExperts; i += 256) (&run_cnt[0][0])[i] = 0;
   const int total_rows = exclusive_scan_256(off, my_cnt);
   if (blockIdx.x == 0) {
     const int e = threadIdx.x;
@@ -505,6 +521,8 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   const int S = p.s.S;
   const int nseg = p.layer0_order == 1 ? S : 1;
   const bool local0 = p.layer0_order == 0, local1 = p.layer1_order == 0;
+  __shared__ int32_t seg_lds[kMaxSegments + 1];
+  if (tid <= S) seg_lds[tid] = p.seg_offsets[tid];
   if (tid < 3) L.cls_count[tid] = 0;
   if (tid < kXcds) L.q_len_t[tid] = 0;
   for (int i = tid; i < 3 * kMaxExperts; i += 1024) (&L.run_first[0][0])[i] = -1;
@@ -518,7 +536,7 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
     const int r0 = p.ws.tile_row0[m], nr = p.ws.tile_rows[m], kd = p.ws.tile_kind[m];
     const int t = p.ws.row_token[r0 + nr - 1];
     int s = 0;
-    while (s + 1 < S && p.seg_offsets[s + 1] <= t) s++;
+    while (s + 1 < S && seg_lds[s + 1] <= t) s++;
     L.row0[m] = r0;
     L.rows[m] = (uint16_t)nr;
     L.kind[m] = (uint8_t)kd;
