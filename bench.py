@@ -133,6 +133,7 @@ def main() -> int:
                                f"{'SwiGLU' if cfg.act == wl.ACT_SWIGLU else 'GELU'} S={cfg.S} seed={cfg.seed}",
                    "tile_m": moe.moe_plan_get_option(plan, "tile_m"), "n_dm": moe.moe_plan_get_option(plan, "n_dm"),
                    "layer1_order": moe.moe_plan_get_option(plan, "layer1_order"),
+                   "gather": "fused into layer0's operand loads (no separate phase, no materialised copy)",
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},
         "phases_us": {"index_build": round(phase_ms[0] * 1e3, 1), "layer0_gemm": round(phase_ms[1] * 1e3, 1),
                       "layer1_gemm": round(phase_ms[2] * 1e3, 1), "combine": round(phase_ms[3] * 1e3, 1),
