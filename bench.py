@@ -134,6 +134,7 @@ def main() -> int:
                    "tile_m": moe.moe_plan_get_option(plan, "tile_m"), "n_dm": moe.moe_plan_get_option(plan, "n_dm"),
                    "layer1_order": moe.moe_plan_get_option(plan, "layer1_order"),
                    "gather": "fused into layer0's operand loads (no separate phase, no materialised copy)",
+                   "device": device_info(torch),
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},
         "phases_us": {"index_build": round(phase_ms[0] * 1e3, 1), "layer0_gemm": round(phase_ms[1] * 1e3, 1),
                       "layer1_gemm": round(phase_ms[2] * 1e3, 1), "combine": round(phase_ms[3] * 1e3, 1),
@@ -146,11 +147,35 @@ def main() -> int:
                      "traffic": traffic},
     }
 
+    # what this board sustains with the same MFMA instruction from registers, and its copy rate: context for the
+    # fractions above (the published peak assumes a clock the board does not hold under this load)
+    probe_scratch = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    copy_src = torch.ones(1 << 28, dtype=torch.uint8, device="cuda")
+    copy_dst = torch.empty_like(copy_src)
+    mfma_random = moe.moe_probe_mfma(True, 100000, probe_scratch)      # about 0.1 s of load: the clock settles
+    result["device_ceilings"] = {
+        "mfma_loop_random_bf16_tflops": round(mfma_random, 1),
+        "mfma_loop_zeros_tflops": round(moe.moe_probe_mfma(False, 100000, probe_scratch), 1),
+        "copy_gbps_read_plus_write": round(moe.moe_probe_copy(copy_dst, copy_src), 1),
+        "layer_frac_of_mfma_loop_random": round(tflops / mfma_random, 4),
+    }
+    del copy_src, copy_dst
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, ids.cpu().numpy(), w.cpu().numpy(), out, args.cpu_sample_tokens)
     print(json.dumps(result, ensure_ascii=False))
     moe.moe_plan_destroy(plan)
     return 0
+
+
+def device_info(torch):
+    """Name, compute units and maximum clock of the GPU, as the runtime reports them."""
+    pr = torch.cuda.get_device_properties(0)
+    info = {"name": pr.name, "compute_units": pr.multi_processor_count}
+    clock_khz = getattr(pr, "clock_rate", None)
+    if clock_khz:
+        info["max_clock_mhz"] = round(clock_khz / 1e3)
+    return info
 
 
 def cpu_baseline(cfg, inp, ids, w, out_gpu, n_tokens):

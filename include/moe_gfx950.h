@@ -153,6 +153,19 @@ int moe_plan_phase_times(moe_plan_t *plan, float *ms, int32_t *n_steps);
  * [1].  Does not reset the recording; waits for the recorded forwards to finish. */
 int moe_plan_forward_times(moe_plan_t *plan, float *ms, int32_t capacity, int32_t *n_steps);
 
+/* Measurement aids (no part of the paper's method): ceilings of the device, measured by the library's own probe
+ * kernels, to read the layer's figures against.  Both create and destroy two events, enqueue on the given stream
+ * and wait for their own work to finish.
+ * moe_probe_mfma: a register-only loop of v_mfma_f32_32x32x16_bf16, 16 accumulator blocks per wavefront, one
+ *   workgroup of 4 wavefronts per compute unit, iters x 16 instructions per wavefront; random_data != 0: random bf16
+ *   operands, else zeros (zeros draw less power and clock higher).  scratch: dev, at least compute units x 1 KiB
+ *   (overwritten).  tflops: host [1].
+ * moe_probe_copy: plain device copy of bytes (multiple of 16, both pointers 16-byte aligned) from src to dst;
+ *   gbytes_per_s: host [1], bytes read plus bytes written per second. */
+int moe_probe_mfma(int32_t random_data, int32_t iters, void *scratch, size_t scratch_bytes, float *tflops,
+                   void *hip_stream);
+int moe_probe_copy(void *dst, const void *src, size_t bytes, float *gbytes_per_s, void *hip_stream);
+
 /* Status word written by the kernels of the last forward (0, or MOE_ERR_TIMEOUT when a bounded
  * flag wait expired).  Synchronises the stream. */
 int moe_last_device_status(const moe_plan_t *plan, const void *workspace, void *hip_stream);

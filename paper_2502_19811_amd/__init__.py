@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     moe_plan_set_option,
     moe_plan_workspace_bytes,
     moe_play_arrival,
+    moe_probe_copy,
+    moe_probe_mfma,
     moe_receive_buffer_bytes,
     moe_route_topk,
     moe_status_string,

@@ -20,6 +20,7 @@ EXPORTS = [
     "moe_plan_workspace_bytes", "moe_plan_max_tiles", "moe_receive_buffer_bytes", "moe_route_topk",
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
     "moe_status_string", "moe_plan_phase_times", "moe_plan_forward_times", "moe_play_arrival",
+    "moe_probe_mfma", "moe_probe_copy",
 ]
 
 
@@ -78,6 +79,10 @@ def load_library():
     lib.moe_plan_phase_times.restype = C.c_int
     lib.moe_plan_forward_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
     lib.moe_plan_forward_times.restype = C.c_int
+    lib.moe_probe_mfma.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, C.POINTER(C.c_float), vp]
+    lib.moe_probe_mfma.restype = C.c_int
+    lib.moe_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_float), vp]
+    lib.moe_probe_copy.restype = C.c_int
     lib.moe_play_arrival.argtypes = [C.c_void_p, vp, vp, u32p, u32p, C.c_uint32, C.c_double, C.c_int32, vp]
     lib.moe_play_arrival.restype = C.c_int
     lib.moe_status_string.argtypes = [C.c_int]
@@ -194,3 +199,19 @@ def moe_plan_forward_times(plan: int, capacity: int = 64):
     n = C.c_int32()
     _check(load_library().moe_plan_forward_times(plan, ms, capacity, C.byref(n)), "moe_plan_forward_times")
     return [float(ms[i]) for i in range(n.value)]
+
+
+def moe_probe_mfma(random_data: bool, iters: int, scratch, stream=None) -> float:
+    """TFLOP/s of the library's register-only bf16 MFMA loop on this device (scratch: a device tensor of >= 1 MiB)."""
+    out = C.c_float()
+    _check(load_library().moe_probe_mfma(int(bool(random_data)), iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                         C.byref(out), _stream(stream)), "moe_probe_mfma")
+    return float(out.value)
+
+
+def moe_probe_copy(dst, src, stream=None) -> float:
+    """GB/s (read + written) of a plain device copy of src into dst."""
+    out = C.c_float()
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().moe_probe_copy(_ptr(dst), _ptr(src), nbytes, C.byref(out), _stream(stream)), "moe_probe_copy")
+    return float(out.value)

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmoe_gfx950.so")
-SOURCES = ["moe_api.hip", "index_build.hip", "grouped_gemm.hip"]
+SOURCES = ["moe_api.hip", "index_build.hip", "grouped_gemm.hip", "probes.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

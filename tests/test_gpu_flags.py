@@ -134,3 +134,22 @@ def test_paced_arrival_by_a_producer_workgroup():
     assert run.status == 0
     assert flags.cpu().tolist() == [3] * cfg.S and counters.cpu().tolist() == [0] * cfg.S
     np.testing.assert_array_equal(run.out, base.out)
+
+
+def test_device_probes_report_plausible_ceilings():
+    import torch
+    import paper_2502_19811_amd as moe
+    scratch = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    rnd = moe.moe_probe_mfma(True, 4000, scratch)
+    zer = moe.moe_probe_mfma(False, 4000, scratch)
+    print(f"mfma loop: random {rnd:.0f} TFLOP/s, zeros {zer:.0f} TFLOP/s", flush=True)
+    assert 500.0 < rnd < 2600.0 and 500.0 < zer < 2600.0      # below the 2.5 PFLOP/s the data sheet states
+    src = torch.arange(1 << 24, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    gbps = moe.moe_probe_copy(dst, src)
+    print(f"copy: {gbps:.0f} GB/s", flush=True)
+    assert torch.equal(dst, src) and 500.0 < gbps < 8000.0
+    with pytest.raises(moe.MoEError):
+        moe.moe_probe_mfma(True, 0, scratch)
+    with pytest.raises(moe.MoEError):
+        moe.moe_probe_mfma(True, 100, torch.zeros(16, dtype=torch.uint8, device="cuda"))
