@@ -12,7 +12,9 @@
 //  * A is read from LDS with ds_read_b128 (K-contiguous rows, XOR-swizzled by row), B (stored K x N as the
 //    weights are) with ds_read_b64_tr_b16, which hands every lane the 4 K-consecutive values of its column;
 //  * a layer0 tile waits for the ready flag of the source segment of its last row (Section 2.2.1: a tile
-//    cannot start before all of its tokens have arrived).
+//    cannot start before all of its tokens have arrived);
+//  * the tile schedules are built on the device (index_build.hip): one queue of 32-byte item records per XCD,
+//    taken with one atomic per tile, a tile ahead, and stolen from the other XCDs' queues at the end.
 #include "moe_internal.h"
 
 namespace moe {
@@ -401,8 +403,9 @@ __device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t
 // One tile of BM = WM*MT*32 rows by 256 columns: address set-up and first loads, main loop, epilogue.  While the
 // tile runs the workgroup finds out what its next tile is without waiting for any of the round trips: the queue
 // atomic is issued up front; once the last operand load has landed (48 MFMAs before the end) its result is shared
-// through LDS and the item record is requested; the rows of A the next tile gathers are requested before the
-// epilogue.  next.idx = -1: no further tile.
+// through LDS and the item record is requested.  A full-height tile followed by another one also starts the
+// successor's first operand stages during its own epilogue (next.pre = 1); otherwise only the rows of A the next
+// tile gathers are requested, after the epilogue.  next.idx = -1: no further tile.
 template <int WM, int MT, int NT, int MODE>
 __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, const Tile& cur,
                                          Tile& next, int xcd, const Queue& q, int& pending_panel,
