@@ -153,3 +153,31 @@ def test_device_probes_report_plausible_ceilings():
         moe.moe_probe_mfma(True, 0, scratch)
     with pytest.raises(moe.MoEError):
         moe.moe_probe_mfma(True, 100, torch.zeros(16, dtype=torch.uint8, device="cuda"))
+
+
+def test_one_plan_and_workspace_serve_different_routings_in_a_row():
+    """Nothing of a forward survives into the next one on the same plan and workspace: a second forward with another
+    routing (other counts, other tile table, fewer tiles) and then the first routing again give what fresh runs give."""
+    H, cfg, inp, ids, w, layer = _setup()
+    layer.forward()
+    first = layer.results()
+    ref1 = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    # second routing: everything to experts 0 and 5, uneven weights
+    ids2 = np.tile(np.array([[5, 0]], np.int32), (cfg.T, 1))
+    w2 = np.tile(np.array([[0.9, 0.1]], np.float32), (cfg.T, 1))
+    layer.ids.copy_(torch.from_numpy(ids2).cuda())
+    layer.w.copy_(torch.from_numpy(w2).cuda())
+    layer.forward()
+    second = layer.results()
+    assert second.status == 0 and second.counts.tolist() == [cfg.T, 0, 0, 0, 0, cfg.T, 0, 0]
+    a, b = H.error_metrics(second.out, orc.moe_layer(inp.x, inp.W1, inp.W2, ids2, w2, cfg.act))
+    assert a <= H.REL_TOL and b <= H.REL_TOL
+    layer.ids.copy_(torch.from_numpy(ids).cuda())
+    layer.w.copy_(torch.from_numpy(w).cuda())
+    layer.forward()
+    third = layer.results()
+    layer.close()
+    np.testing.assert_array_equal(third.out, first.out)
+    np.testing.assert_array_equal(third.perm, first.perm)
+    a, b = H.error_metrics(third.out, ref1)
+    assert a <= H.REL_TOL and b <= H.REL_TOL
