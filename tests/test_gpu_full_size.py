@@ -74,3 +74,21 @@ def test_full_size_token_reversal_moves_every_row_bit_for_bit(name):
     l2.forward(); r2 = l2.results(); l2.close()
     assert r2.status == 0
     np.testing.assert_array_equal(r2.out[::-1], base.out)
+
+
+def test_full_size_whole_output_against_the_oracle():
+    """The Mixtral-shaped workload bench.py times, every output element against the oracle (about 6 TFLOP in fp64 on
+    the host: seconds on the GPU machine's cores)."""
+    import gpu_harness as H
+    cfg = wl.CONFIGS["mixtral"]
+    print("whole-output parity mixtral: generating inputs", flush=True)
+    inp = wl.make_inputs(cfg, threads=16)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    layer = H.GpuLayer(cfg, inp, ids, w)
+    layer.forward(); run = layer.results(); layer.close()
+    assert run.status == 0
+    print("  oracle on all tokens", flush=True)
+    ref = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    a, b = H.error_metrics(run.out, ref)
+    print(f"  err {a:.3e} {b:.3e}", flush=True)
+    assert a <= H.REL_TOL and b <= H.REL_TOL
