@@ -440,8 +440,8 @@ __global__ __launch_bounds__(1024) void k_index_schedule_large(IndexParams p) {
 // the size limit (and with simpler orders).
 //
 // Locality order (layer0 with order 0, layer1 with the separate combine kernel): per tile height, an expert's
-// M-tiles are cut into blocks of up to 8; block b goes to XCD b % 8, whose queue holds its blocks one after the
-// other, tallest first.  Inside a block of G M-tiles the column tiles ascend and the block's M-tiles are the inner
+// M-tiles are cut into blocks of up to 8; the blocks are dealt to the XCDs, whose queues hold their blocks one after
+// the other, tallest first.  Inside a block of G M-tiles the column tiles ascend and the block's M-tiles are the inner
 // loop.  The 32 workgroups of an XCD, taking consecutive items, then work on G M-tiles x about 32/G column tiles of
 // one expert wherever in the block they are, and share both operands in their L2; an expert with few rows is
 // streamed through one XCD only (its weight panels are fetched once).
@@ -454,6 +454,9 @@ struct ScheduleLds {
   uint16_t ord0[kTileCap];     // layer0 order: position -> tile
   uint16_t ord1[kTileCap];     // layer1 order (height class, then table order)
   uint16_t blk_g[kTileCap];    // M-tiles of block b
+  uint16_t blk_ord[kTileCap];  // blocks in dealing order: height class, then larger blocks first
+  uint8_t blk_q[kTileCap];     // XCD queue of block b
+  uint8_t blk_key[kTileCap + 4];
   uint8_t expert[kTileCap];
   uint8_t kind[kTileCap];
   uint8_t ready[kTileCap];
@@ -509,7 +512,7 @@ __device__ inline void emit_blocks(const ScheduleLds& L, const uint16_t* ord, It
     const int m = ord[i], c = 2 - L.kind[m], e = L.expert[m];
     const int j = i - L.run_first[c][e];
     const int b = L.blk_base[c * kMaxExperts + e] + (j >> 3), g = L.blk_g[b], jm = j & 7;
-    const int pos = (L.q_base_t[b & (kXcds - 1)] + L.blk_off[b]) * n_tiles_n + n * g + jm;
+    const int pos = (L.q_base_t[L.blk_q[b]] + L.blk_off[b]) * n_tiles_n + n * g + jm;
     items[pos] = make_item_lds(L, m, n);
   }
 }
@@ -612,15 +615,31 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
     for (int i = tid; i < n_tiles; i += 1024) {
       const int m = ord1[i], c = 2 - L.kind[m], e = L.expert[m];
       const int j = i - L.run_first[c][e], cnt = L.run_last[c][e] - L.run_first[c][e] + 1;
-      if ((j & 7) == 0) L.blk_g[L.blk_base[c * kMaxExperts + e] + (j >> 3)] = (uint16_t)min(8, cnt - j);
+      if ((j & 7) == 0) {
+        const int b = L.blk_base[c * kMaxExperts + e] + (j >> 3), g = min(8, cnt - j);
+        L.blk_g[b] = (uint16_t)g;
+        L.blk_key[b] = (uint8_t)(c * 8 + (8 - g));   // height class first, inside it the larger blocks first
+      }
     }
-    __syncthreads();
     const int n_blocks = L.n_blocks;
-    for (int b = tid; b < n_blocks; b += 1024) {
+    for (int b = n_blocks + tid; b < n_blocks + 4; b += 1024) L.blk_key[b] = 0xff;
+    __syncthreads();
+    // The blocks are dealt to the XCD queues in that order, back and forth (0..7, 7..0, ...): with the sizes
+    // descending this keeps the queues level even when the experts' loads differ a lot, which round-robin does not
+    // (what is left uneven, the workgroups even out by taking from other XCDs' queues at the end).
+    rank_sort(L.blk_key, L.blk_ord, n_blocks, tid);
+    __syncthreads();
+    for (int pos = tid; pos < n_blocks; pos += 1024) {
+      const int r = pos / kXcds, i = pos % kXcds;
+      const int x = (r & 1) ? kXcds - 1 - i : i;
       int off = 0;
-      for (int q = b - kXcds; q >= 0; q -= kXcds) off += L.blk_g[q];
+      for (int r2 = 0; r2 < r; r2++) off += L.blk_g[L.blk_ord[r2 * kXcds + ((r2 & 1) ? kXcds - 1 - x : x)]];
+      const int b = L.blk_ord[pos];
       L.blk_off[b] = off;
-      if (b + kXcds >= n_blocks) L.q_len_t[b & (kXcds - 1)] = off + L.blk_g[b];
+      L.blk_q[b] = (uint8_t)x;
+      // the queue's last block: no later round has a block for this queue
+      const int next = (r + 1) * kXcds + (((r + 1) & 1) ? kXcds - 1 - x : x);
+      if (next >= n_blocks) L.q_len_t[x] = off + L.blk_g[b];
     }
     __syncthreads();
     if (tid == 0) {
