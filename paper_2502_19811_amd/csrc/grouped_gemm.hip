@@ -595,73 +595,83 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 
   // Epilogue.  The MFMAs ran with the operands swapped (B fragment first), so a lane holds, for output row
   // lane & 31 of each 32x32 block, the columns 8*(i/4) + 4*(lane/32) + i%4: four consecutive columns per group of
-  // four accumulator registers.  One 32-row block at a time, the wavefront's part of the tile is staged in LDS as
-  // bf16 (8-byte writes, 16-byte chunks XOR-swizzled by row) and written out in full 16-byte pieces, whole rows at
-  // a time; 2-byte stores straight from the accumulators cost a tenth of the tile's time.
+  // four accumulator registers.  The wavefront's part of the tile goes out in pieces of 32 rows x 128 bytes (64 bytes
+  // where the wavefront has a single 32-column block of output): a piece
+  // is staged in LDS as bf16 (8-byte writes, 16-byte chunks XOR-swizzled by row) and written out in full 16-byte
+  // chunks, 8 rows of 128 bytes per store instruction; 2-byte stores straight from the accumulators cost a tenth of
+  // the tile's time.  Two staging buffers per wavefront: while piece s is converted and staged, the chunks of piece
+  // s-1 are on their way back from LDS, so that only the first and the last piece pay an LDS round trip.
   constexpr int OUT_NT = (MODE == MODE_L0_SWIGLU) ? NT / 2 : NT;   // 32-column blocks of output per wavefront
-  constexpr int RB = OUT_NT * 64;                                   // bytes per staged row
-  constexpr int NC = RB / 16;                                       // 16-byte chunks per staged row
-  constexpr int RPB = RB >= 256 ? 1 : 256 / RB;                     // rows per 256 bytes of LDS banks
-  const uint32_t cbase = lds0 + kStagingOffset + w * (32 * RB);     // 32 rows x RB bytes per wavefront (<= 8 KiB)
+  constexpr int PW = OUT_NT >= 2 ? 2 : 1;                           // 32-column blocks per piece
+  constexpr int PH = OUT_NT / PW;                                   // pieces per 32-row block
+  constexpr int PRB = PW * 64;                                      // bytes per staged row of a piece
+  constexpr int PNC = PRB / 16;                                     // 16-byte chunks per staged row
+  constexpr int RPB = 256 / PRB;                                    // rows per 256 bytes of LDS banks
+  constexpr int NST = 32 * PNC / 64;                                // 16-byte stores per lane and piece
+  constexpr int NPIECE = MT * PH;
+  static_assert(OUT_NT % PW == 0, "pieces tile the wavefront's columns");
+  const uint32_t cbase = lds0 + kStagingOffset + w * (2 * 32 * PRB);   // 2 buffers x 32 rows x 128 bytes per wavefront
   int lane_e = lane;   // opaque again: the epilogue's addresses are computed here, not before the main loop
   asm volatile("" : "+v"(lane_e));
   const int col_base = (MODE == MODE_L0_SWIGLU) ? col0 + wn * (NT * 16) : col0 + wn * (NT * 32);
+  const bool full = nrows == BM;
+  // converts piece s (row block s / PH, column blocks 2 * (s % PH) and the next) and stages it in buffer s & 1
+  auto stage_piece = [&](int s) {
+    const int mt = s / PH, nt0 = (s % PH) * PW;
+    const int m = lane_e & 31, half = lane_e >> 5;
+    const uint32_t row_addr = cbase + (s & 1) * (32 * PRB) + m * PRB + half * 8;
+    const int sw = (m / RPB) & (PNC - 1);
 #pragma unroll
-  for (int mt = 0; mt < MT; mt++) {
-    __builtin_amdgcn_sched_barrier(0);   // one 32-row block at a time: keeps the address temporaries few
-    {
-      const int m = lane_e & 31, half = lane_e >> 5;
-      const uint32_t row_addr = cbase + m * RB + half * 8;
-      const int sw = (m / RPB) & (NC - 1);
+    for (int n2 = 0; n2 < PW; n2++) {
+      const int nt = nt0 + n2;
+      if (MODE == MODE_L0_GELU) __builtin_amdgcn_sched_barrier(0);  // bounds the live activation temporaries
 #pragma unroll
-      for (int nt = 0; nt < OUT_NT; nt++) {
-        if (MODE == MODE_L0_GELU) __builtin_amdgcn_sched_barrier(0);  // bounds the live activation temporaries
+      for (int qd = 0; qd < 4; qd++) {
+        float v[4];
 #pragma unroll
-        for (int qd = 0; qd < 4; qd++) {
-          float v[4];
-#pragma unroll
-          for (int i = 0; i < 4; i++) {
-            if (MODE == MODE_L0_SWIGLU) v[i] = silu(acc[mt][nt][qd * 4 + i]) * acc[mt][nt + NT / 2][qd * 4 + i];
-            else if (MODE == MODE_L0_GELU) v[i] = gelu_erf(acc[mt][nt][qd * 4 + i]);
-            else v[i] = acc[mt][nt][qd * 4 + i];
-          }
-          bf16x2 lo = {(__bf16)v[0], (__bf16)v[1]}, hi = {(__bf16)v[2], (__bf16)v[3]};
-          u32x2 pk = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-          const int chunk = nt * 4 + qd;
-          *(u32x2 __attribute__((address_space(3)))*)(uintptr_t)(row_addr + ((chunk ^ sw) << 4)) = pk;
+        for (int i = 0; i < 4; i++) {
+          if (MODE == MODE_L0_SWIGLU) v[i] = silu(acc[mt][nt][qd * 4 + i]) * acc[mt][nt + NT / 2][qd * 4 + i];
+          else if (MODE == MODE_L0_GELU) v[i] = gelu_erf(acc[mt][nt][qd * 4 + i]);
+          else v[i] = acc[mt][nt][qd * 4 + i];
         }
+        bf16x2 lo = {(__bf16)v[0], (__bf16)v[1]}, hi = {(__bf16)v[2], (__bf16)v[3]};
+        u32x2 pk = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+        const int chunk = n2 * 4 + qd;
+        *(u32x2 __attribute__((address_space(3)))*)(uintptr_t)(row_addr + ((chunk ^ sw) << 4)) = pk;
       }
     }
-    {
-      const int c = lane_e % NC;
-      constexpr int NST = 32 * NC / 64;   // 16-byte stores per lane and 32-row block
-      auto staged = [&](int it) {
-        const int r = it * (64 / NC) + lane_e / NC;
-        return *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
-            cbase + r * RB + ((c ^ ((r / RPB) & (NC - 1))) << 4));
-      };
-      if (nrows == BM) {
-        // a full tile (the usual case): all staged chunks are read back first, then stored, so that the stores
-        // do not each wait for an LDS round trip of their own
-        u32x4 v[NST];
+  };
+  // reads the 16-byte chunks of piece s this lane stores (rows it * 8 + lane / 8, chunk lane % 8)
+  auto fetch_piece = [&](int s, u32x4* v) {
+    const int c = lane_e % PNC;
 #pragma unroll
-        for (int it = 0; it < NST; it++) v[it] = staged(it);
-#pragma unroll
-        for (int it = 0; it < NST; it++) {
-          const int grow = wm * (MT * 32) + mt * 32 + it * (64 / NC) + lane_e / NC;
-          *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v[it];
-        }
-      } else {
-#pragma unroll
-        for (int it = 0; it < NST; it++) {
-          const u32x4 v = staged(it);
-          const int grow = wm * (MT * 32) + mt * 32 + it * (64 / NC) + lane_e / NC;
-          if (grow < nrows) *(u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + c * 8) = v;
-        }
-      }
+    for (int it = 0; it < NST; it++) {
+      const int r = it * (64 / PNC) + lane_e / PNC;
+      v[it] = *(const u32x4 __attribute__((address_space(3)))*)(uintptr_t)(
+          cbase + (s & 1) * (32 * PRB) + r * PRB + ((c ^ ((r / RPB) & (PNC - 1))) << 4));
     }
+  };
+  auto store_piece = [&](int s, const u32x4* v) {
+    const int mt = s / PH, ph = s % PH;
+    const int c = lane_e % PNC;
+#pragma unroll
+    for (int it = 0; it < NST; it++) {
+      const int grow = wm * (MT * 32) + mt * 32 + it * (64 / PNC) + lane_e / PNC;
+      u32x4* dst = (u32x4*)(p.C + (size_t)(row0 + grow) * p.ldc + col_base + ph * (PW * 32) + c * 8);
+      if (full) *dst = v[it];
+      else if (grow < nrows) *dst = v[it];
+    }
+  };
+  stage_piece(0);
+#pragma unroll
+  for (int s = 1; s <= NPIECE; s++) {
+    __builtin_amdgcn_sched_barrier(0);   // one piece at a time: keeps the address temporaries few
+    u32x4 v[NST];
+    fetch_piece(s - 1, v);
+    if (s < NPIECE) stage_piece(s);
+    store_piece(s - 1, v);
     if constexpr (kCanPre) {
-      if (mt == 0 && do_pre) {
+      if (s == PH && do_pre) {   // the first 32-row block is out
         if (flags_on) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
         LoadState ls_next;
         setup_and_issue<WM, MT, NT, MODE>(p, lds0, next, ls_next, lane_e, w, true);
