@@ -510,7 +510,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // Full-height tiles start the loads of a full-height successor during their own epilogue, which needs the
   // successor's segment to be there already: the ready flags are sampled here (lane s of the first wavefront reads
   // flag s) and looked at when the successor is known.  A flag raised later than this only costs the early start.
-  constexpr bool kCanPre = WM == 2 && MT == 4 && MODE != MODE_L0_GELU;   // (the GELU variant has no registers left for it)
+  constexpr bool kCanPre = WM == 2 && MT == 4;
   const bool flags_on = MODE != MODE_L1 && p.seg_ready != nullptr;
   uint32_t flag_v = 0;
   if (kCanPre && flags_on && tid < p.n_segments)

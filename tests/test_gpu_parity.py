@@ -105,3 +105,22 @@ def test_index_outputs_full_size(H, name):
         assert abs(run.counts.mean() - 2048) < 1e-9 and run.counts.min() > 1800
     if name == "skewed":
         assert run.counts[0] / cfg.R > 0.3   # the popular expert takes about 40 % of the rows
+
+
+@pytest.mark.parametrize("name", ["gelu_tall", "swiglu_tall", "wide_rows", "ragged_swiglu"])
+def test_few_workgroups_walk_many_tiles(H, name):
+    """With 8 workgroups every workgroup processes many tiles in a row, so the hand-over between tiles (the early
+    start of a full-height successor included) is exercised for every kernel variant."""
+    cfg = next(c for c in SMALL_CASES if c.name == name)
+    inp = wl.make_inputs(cfg, threads=4)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    ref = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    for opts in ({"n_cu": 8}, {"n_cu": 8, "layer1_order": 1}, {"n_cu": 9, "tile_m": 128}):
+        layer = H.GpuLayer(cfg, inp, ids, w, opts)
+        layer.forward()
+        run = layer.results()
+        layer.close()
+        assert run.status == 0
+        a, b = H.error_metrics(run.out, ref)
+        print(f"  {name} {opts}: err {a:.3e} {b:.3e}", flush=True)
+        assert a <= H.REL_TOL and b <= H.REL_TOL
