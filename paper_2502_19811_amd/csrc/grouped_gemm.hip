@@ -403,7 +403,7 @@ __device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t
 // One tile of BM = WM*MT*32 rows by 256 columns: address set-up and first loads, main loop, epilogue.  While the
 // tile runs the workgroup finds out what its next tile is without waiting for any of the round trips: the queue
 // atomic is issued up front; once the last operand load has landed (48 MFMAs before the end) its result is shared
-// through LDS and the item record is requested.  A full-height tile followed by another one also starts the
+// through LDS and the item record is requested.  A tile followed by one of the same height also starts the
 // successor's first operand stages during its own epilogue (next.pre = 1); otherwise only the rows of A the next
 // tile gathers are requested, after the epilogue.  next.idx = -1: no further tile.
 template <int WM, int MT, int NT, int MODE>
@@ -507,10 +507,11 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // operand loads of the first stages were issued before (by the previous tile, or by the kernel for the first).
   int next_raw = 0;
   if (tid == 0) next_raw = take_from(p, xcd, q.own_len, q.own_base);
-  // Full-height tiles start the loads of a full-height successor during their own epilogue, which needs the
-  // successor's segment to be there already: the ready flags are sampled here (lane s of the first wavefront reads
+  // A tile starts the loads of a successor of its own height during its epilogue, which needs the successor's
+  // segment to be there already: the ready flags are sampled here (lane s of the first wavefront reads
   // flag s) and looked at when the successor is known.  A flag raised later than this only costs the early start.
-  constexpr bool kCanPre = WM == 2 && MT == 4;
+  constexpr bool kCanPre = true;   // (kept as a switch: the early start costs about 30 VGPRs)
+  constexpr int kKind = (WM == 2 && MT == 4) ? 2 : (WM == 2 ? 1 : 0);   // height class of this variant's tiles
   const bool flags_on = MODE != MODE_L1 && p.seg_ready != nullptr;
   uint32_t flag_v = 0;
   if (kCanPre && flags_on && tid < p.n_segments)
@@ -589,7 +590,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // early start of the successor (see above): its gather rows are requested now, its first stages after the first
   // 32-row block of the epilogue, into the three stages the epilogue does not use
   bool do_pre = false;
-  if (kCanPre && next.idx >= 0 && next.rec.kind == 2 && ((ready_mask >> (next.rec.ready_seg & 63)) & 1)) do_pre = true;
+  if (kCanPre && next.idx >= 0 && next.rec.kind == kKind && ((ready_mask >> (next.rec.ready_seg & 63)) & 1)) do_pre = true;
   next.pre = do_pre;
   if (kCanPre && do_pre) load_arows<MODE>(p, next, lane, w);
 
