@@ -320,7 +320,10 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     a.seg_ready = seg_ready;
     a.ready_epoch = ready_epoch;
     a.n_segments = s.S;
-    a.n_mfma = p->n_cu;
+    // no more workgroups than there can be items (small batches are bound by the launch, not by the work)
+    const int64_t max_items0 = (int64_t)p->max_tiles * p->n_tiles_n0;
+    const int grid0 = max_items0 < p->n_cu ? (max_items0 < 8 ? 8 : (int)max_items0) : p->n_cu;
+    a.n_mfma = grid0;
     a.queue_heads = ws.status + 8;
     a.queue_len = ws.status + 24;
     if (p->layer0_order == 0 && !uses_large_schedule(p->max_tiles, p->large_schedule)) {
@@ -330,7 +333,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
       a.queue_base = nullptr;          // queue x = list positions x, x + 8, ...
       a.queue_stride = kXcds;
     }
-    if (launch_layer0(a, s.act, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_layer0(a, s.act, grid0, st) != hipSuccess) return MOE_ERR_HIP;
   }
 
   if (!mark(2)) return MOE_ERR_HIP;
@@ -351,7 +354,10 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.panel_done = ws.panel_done;
     int n_dm = fused ? (p->n_dm >= 0 ? p->n_dm : default_n_dm(s)) : 0;
     if (n_dm > p->n_cu - 8) n_dm = p->n_cu - 8;
-    b.n_mfma = p->n_cu - n_dm;
+    const int64_t max_items1 = (int64_t)p->max_tiles * p->n_tiles_n1;
+    int grid1 = p->n_cu;
+    if (!fused && max_items1 < grid1) grid1 = max_items1 < 8 ? 8 : (int)max_items1;
+    b.n_mfma = grid1 - n_dm;
     b.fused_combine = fused ? 1 : 0;
     b.batch_publish = (fused && n_dm == 0 && s.H / kTileN <= 128) ? 1 : 0;
     b.inv_perm = ws.inv_perm;
@@ -362,7 +368,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.queue_len = ws.status + 32;
     b.queue_base = ws.status + 40;
     b.queue_stride = 1;
-    if (launch_layer1(b, p->n_cu, st) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_layer1(b, grid1, st) != hipSuccess) return MOE_ERR_HIP;
   }
   if (!mark(3)) return MOE_ERR_HIP;
   if ((p->phases & 8) && !(fused && (p->phases & 4))) {
