@@ -77,6 +77,10 @@ int moe_plan_destroy(moe_plan_t *plan);
  *   "n_cu"         workgroups of the persistent kernels (default: compute units of the device)
  *   "profile"      1: every forward records HIP events on its stream before and after each phase
  *                  (this call then creates the events; read them with moe_plan_phase_times)
+ *   "block_m"      1..8: M-tiles of one expert that form a block of the default tile order; a block's items go to
+ *                  one XCD (default 4: the 32 workgroups of an XCD then work on 4 M-tiles x 8 column tiles, and
+ *                  two XCDs sweep the same weight panels of an expert with 8 M-tiles at the same time, the second
+ *                  finding them in the Infinity Cache)
  *   "large_schedule" 1: build the tile schedules with the one-workgroup kernel that has no limit on the
  *                  number of M-tiles (the default picks it only above 2048 tiles); its orders are simpler
  *                  (less operand sharing inside an XCD), the results are the same bit for bit

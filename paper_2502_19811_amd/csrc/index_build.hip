@@ -440,8 +440,8 @@ __global__ __launch_bounds__(1024) void k_index_schedule_large(IndexParams p) {
 // the size limit (and with simpler orders).
 //
 // Locality order (layer0 with order 0, layer1 with the separate combine kernel): per tile height, an expert's
-// M-tiles are cut into blocks of up to 8; the blocks are dealt to the XCDs, whose queues hold their blocks one after
-// the other, tallest first.  Inside a block of G M-tiles the column tiles ascend and the block's M-tiles are the inner
+// M-tiles are cut into blocks of up to block_m (4 by default); the blocks are dealt to the XCDs, whose queues hold
+// their blocks one after the other, tallest first.  Inside a block of G M-tiles the column tiles ascend and the block's M-tiles are the inner
 // loop.  The 32 workgroups of an XCD, taking consecutive items, then work on G M-tiles x about 32/G column tiles of
 // one expert wherever in the block they are, and share both operands in their L2; an expert with few rows is
 // streamed through one XCD only (its weight panels are fetched once).
@@ -506,12 +506,12 @@ __device__ inline void rank_sort(const uint8_t* key, uint16_t* ord, int n, int t
 
 // Items of one layer in the locality order (see above); n_tiles_n column tiles.
 __device__ inline void emit_blocks(const ScheduleLds& L, const uint16_t* ord, ItemRec* items, int n_tiles, int n_tiles_n,
-                                   int gtid, int gthreads) {
+                                   int block_m, int gtid, int gthreads) {
   for (int w = gtid; w < n_tiles * n_tiles_n; w += gthreads) {
     const int i = w / n_tiles_n, n = w % n_tiles_n;
     const int m = ord[i], c = 2 - L.kind[m], e = L.expert[m];
     const int j = i - L.run_first[c][e];
-    const int b = L.blk_base[c * kMaxExperts + e] + (j >> 3), g = L.blk_g[b], jm = j & 7;
+    const int b = L.blk_base[c * kMaxExperts + e] + j / block_m, g = L.blk_g[b], jm = j % block_m;
     const int pos = (L.q_base_t[L.blk_q[b]] + L.blk_off[b]) * n_tiles_n + n * g + jm;
     items[pos] = make_item_lds(L, m, n);
   }
@@ -524,6 +524,7 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   const int S = p.s.S;
   const int nseg = p.layer0_order == 1 ? S : 1;
   const bool local0 = p.layer0_order == 0, local1 = p.layer1_order == 0;
+  const int block_m = p.block_m;   // M-tiles per block of the locality order (1..8)
   __shared__ int32_t seg_lds[kMaxSegments + 1];
   if (tid <= S) seg_lds[tid] = p.seg_offsets[tid];
   if (tid < 3) L.cls_count[tid] = 0;
@@ -597,7 +598,7 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
       // blocks per (class, expert), then an exclusive prefix sum over the 768 pairs (1024 threads, one each)
       const int c = tid / kMaxExperts, e = tid % kMaxExperts;
       int nb = 0;
-      if (c < 3 && L.run_first[c][e] >= 0) nb = (L.run_last[c][e] - L.run_first[c][e] + 1 + 7) >> 3;
+      if (c < 3 && L.run_first[c][e] >= 0) nb = (L.run_last[c][e] - L.run_first[c][e] + block_m) / block_m;
       L.blk_base[tid] = nb;
       __syncthreads();
       for (int d = 1; d < 1024; d <<= 1) {
@@ -615,8 +616,8 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
     for (int i = tid; i < n_tiles; i += 1024) {
       const int m = ord1[i], c = 2 - L.kind[m], e = L.expert[m];
       const int j = i - L.run_first[c][e], cnt = L.run_last[c][e] - L.run_first[c][e] + 1;
-      if ((j & 7) == 0) {
-        const int b = L.blk_base[c * kMaxExperts + e] + (j >> 3), g = min(8, cnt - j);
+      if (j % block_m == 0) {
+        const int b = L.blk_base[c * kMaxExperts + e] + j / block_m, g = min(block_m, cnt - j);
         L.blk_g[b] = (uint16_t)g;
         L.blk_key[b] = (uint8_t)(c * 8 + (8 - g));   // height class first, inside it the larger blocks first
       }
@@ -662,14 +663,14 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
     }
   }
   if (local0) {
-    emit_blocks(L, ord1, p.ws.items0, n_tiles, p.n_tiles_n0, gtid, gthreads);
+    emit_blocks(L, ord1, p.ws.items0, n_tiles, p.n_tiles_n0, block_m, gtid, gthreads);
   } else {
     // by source segment (Fig. 5): all column tiles of an M-tile in a row; list position i belongs to XCD i % 8
     for (int i = gtid; i < n_tiles * p.n_tiles_n0; i += gthreads)
       p.ws.items0[i] = make_item_lds(L, L.ord0[i / p.n_tiles_n0], i % p.n_tiles_n0);
   }
   if (local1) {
-    emit_blocks(L, ord1, p.ws.items1, n_tiles, p.n_tiles_n1, gtid, gthreads);
+    emit_blocks(L, ord1, p.ws.items1, n_tiles, p.n_tiles_n1, block_m, gtid, gthreads);
   } else {
     // panel-major (Fig. 6): every XCD sweeps its chunk of a height class per group of 4 column panels: the chunk's
     // tiles, each with the 4 panels; panel groups ascend, so all M-tiles of the chunk finish group g before g + 1

@@ -68,6 +68,7 @@ struct IndexParams {
   int32_t layer0_order, layer1_order;
   int32_t max_tiles;             // bound on the M-tiles of this plan
   int32_t force_large_schedule;  // 1: build the schedules with the one-workgroup kernel whatever the size
+  int32_t block_m;               // M-tiles per block of the locality order (1..8)
   int32_t seg_offsets[kMaxSegments + 1];
 };
 
