@@ -6,9 +6,10 @@
 //    GEMM workgroup or a data-movement workgroup, chosen by its index (the division point of Section 3.2.2);
 //  * a GEMM workgroup is 4 wavefronts, one per SIMD; a tile is BM x 256 outputs with BM = 256, 128 or 64, and
 //    accumulates in fp32 with v_mfma_f32_32x32x16_bf16;
-//  * operands go global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no registers in between),
-//    through a ring of 4 stages of depth 32; rows of A are gathered through per-lane row offsets that stay in
-//    registers for the whole tile (the row-index caching of Section 4);
+//  * operands go global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no registers in between):
+//    B through a ring of 4 stages of depth 32, A through a ring of 5 blocks of half the tile's rows by depth 64, so
+//    that a load of A fetches whole 128-byte lines (8 rows per instruction); rows of A are gathered through
+//    per-lane row offsets that stay in registers for the whole tile (the row-index caching of Section 4);
 //  * A is read from LDS with ds_read_b128 (K-contiguous rows, XOR-swizzled by row), B (stored K x N as the
 //    weights are) with ds_read_b64_tr_b16, which hands every lane the 4 K-consecutive values of its column;
 //  * a layer0 tile waits for the ready flag of the source segment of its last row (Section 2.2.1: a tile
@@ -295,7 +296,7 @@ __device__ __forceinline__ void publish_panel(const GemmParams& p, int panel) {
 struct Tile {
   int idx;        // list position, -1: none
   ItemRec rec;
-  int arow[4];    // rows of A this lane loads per stage (layer0: gathered token rows, layer1: rows of h)
+  int arow[8];    // rows of A this lane loads, per half of the tile's rows (layer0: gathered token rows, layer1: rows of h)
   int pre;        // 1: the loads of its first NS-1 stages were issued during the previous tile's epilogue
 };
 __device__ __forceinline__ ItemRec make_uniform(ItemRec r) {
@@ -306,40 +307,56 @@ __device__ __forceinline__ ItemRec make_uniform(ItemRec r) {
 __device__ __forceinline__ ItemRec load_item(const GemmParams& p, int idx) { return make_uniform(p.items[idx]); }
 // Global offsets and running base pointers of a tile's operand loads.
 struct LoadState {
-  uint32_t aoff[4], boff[4];
+  uint32_t aoff[8], boff[4];
   const char* Ab;
   const char* Bb;
 };
 
-constexpr int kStagingOffset = 3 * (256 * BK * 2 + B_STAGE);   // the epilogue stages C in the last 32 KiB of LDS
+// LDS of a tile of BM rows.  A is kept in a ring of kABlocks blocks, a block being one half of the tile's rows by 64
+// values of K (128 bytes per row: whole cache lines of the operand, 8 rows per load instruction; fetching the 64
+// bytes of one K step per row, 16 rows per instruction, is 1-2 % slower).  Block b = 2d + h holds rows [h*BM/2, (h+1)*BM/2) for
+// K steps 2d and 2d+1.  B is kept in a ring of NS stages of one K step behind it.
+constexpr int kABlocks = 5;
+constexpr int a_block_bytes(int bm) { return bm * 64; }
+constexpr int b_ring_offset(int bm) { return kABlocks * a_block_bytes(bm); }
+// The epilogue stages C in 32 KiB that are free at the end of a tile even when the successor's first loads are under
+// way (A blocks 0..2, B stages 0..2): A blocks 3 and 4 of a 256-row tile, the space behind the rings otherwise.
+constexpr int staging_offset(int bm) { return bm == 256 ? 3 * a_block_bytes(bm) : b_ring_offset(bm) + NS * B_STAGE; }
+constexpr int kLdsBytes = b_ring_offset(256) + NS * B_STAGE;   // 144 KiB; covers the smaller tiles' layouts too
+static_assert(staging_offset(128) + 32768 <= kLdsBytes && staging_offset(64) + 32768 <= kLdsBytes, "staging fits");
 
-// Rows of A the lane loads for a tile of the given height class (LA = 1, 2 or 4 loads per stage).
+// Rows of A the lane loads for a tile of the given height class: LA = 1, 2 or 4 loads per block and two blocks (row
+// halves) per tile; a load covers 8 rows, 8 lanes per row.  arow[h * LA + j]: row half h, load j.
 template <int MODE>
 __device__ __forceinline__ void load_arows(const GemmParams& p, Tile& t, int lane, int w) {
   const int la = 1 << t.rec.kind;
 #pragma unroll
-  for (int j = 0; j < 4; j++) {
-    if (j < la) {
-      const int r = (w * la + j) * 16 + (lane >> 2);
+  for (int i = 0; i < 8; i++) {
+    if (i < 2 * la) {
+      const int h = i / la, j = i % la;
+      const int r = h * (32 * la) + (w * la + j) * 8 + (lane >> 3);
       const int sr = t.rec.row0 + (r < t.rec.nrows ? r : t.rec.nrows - 1);   // past the ragged end: the last row again
-      t.arow[j] = MODE != MODE_L1 ? p.a_rows[sr] : sr;
+      t.arow[i] = MODE != MODE_L1 ? p.a_rows[sr] : sr;
     }
   }
 }
 
-// Address set-up of a tile and the loads of its first NS-1 stages.
+// Address set-up of a tile and its first loads: A blocks 0..2 and B stages 0..2, in the order A0 A1 B0 A2 B1 B2.
+// A: lane l of a load fetches the 16 bytes at position (l & 7) ^ ((row / 2) & 7) of its row's 128-byte line, so that
+// the line lands in LDS (linearly, 16 bytes per lane) with its chunks XOR-swizzled by row: the 16 rows one pass of
+// ds_read_b128 touches then fall on distinct banks.
 template <int WM, int MT, int NT, int MODE>
 __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t lds0, const Tile& t, LoadState& ls, int lane,
                                                 int w, bool issue) {
   constexpr int BM = WM * MT * 32;
-  constexpr int A_STAGE = BM * BK * 2;
-  constexpr int STAGE = A_STAGE + B_STAGE;
+  constexpr int A_BLOCK = a_block_bytes(BM);
+  constexpr int B_RING = b_ring_offset(BM);
   constexpr int LA = BM / 64, LB = 4;
 #pragma unroll
-  for (int j = 0; j < LA; j++) {
-    const int r = (w * LA + j) * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((r >> 2) & 3);
-    ls.aoff[j] = (uint32_t)t.arow[j] * p.lda_bytes + c * 16;
+  for (int i = 0; i < 2 * LA; i++) {
+    const int r = (w * LA + i % LA) * 8 + (lane >> 3);   // row inside the block
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    ls.aoff[i] = (uint32_t)t.arow[i] * p.lda_bytes + c * 16;
   }
   const int col0 = (MODE == MODE_L0_SWIGLU) ? t.rec.n_tile * (BN / 2) : t.rec.n_tile * BN;
 #pragma unroll
@@ -363,19 +380,23 @@ __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t ld
   ls.Bb = uniform(p.B + (uint64_t)t.rec.expert * p.b_expert_bytes);
   const size_t bstep = (size_t)BK * p.ldb * 2;
   if (issue) {
+    auto a_block = [&](int b) {
 #pragma unroll
-    for (int s = 0; s < NS - 1; s++) {
+      for (int j = 0; j < LA; j++)
+        dma16(ls.Ab + (b >> 1) * 128, ls.aoff[(b & 1) * LA + j], lds0 + b * A_BLOCK + (w * LA + j) * 1024);
+    };
+    auto b_stage = [&](int st) {
 #pragma unroll
-      for (int j = 0; j < LA; j++) dma16(ls.Ab, ls.aoff[j], lds0 + s * STAGE + (w * LA + j) * 1024);
-#pragma unroll
-      for (int j = 0; j < LB; j++) dma16(ls.Bb, ls.boff[j], lds0 + s * STAGE + A_STAGE + (w * LB + j) * 1024);
-      ls.Ab += BK * 2;
-      ls.Bb += bstep;
-    }
-  } else {
-    ls.Ab += (NS - 1) * BK * 2;
-    ls.Bb += (NS - 1) * bstep;
+      for (int j = 0; j < LB; j++) dma16(ls.Bb + st * bstep, ls.boff[j], lds0 + B_RING + st * B_STAGE + (w * LB + j) * 1024);
+    };
+    a_block(0);
+    a_block(1);
+    b_stage(0);
+    a_block(2);
+    b_stage(1);
+    b_stage(2);
   }
+  ls.Bb += (NS - 1) * bstep;   // ls.Ab stays the row start: the K position of A comes from the block number
 }
 
 // Workgroup-wide: is the source segment of tile t there?  block = true waits for it (up to the spin limit).
@@ -413,11 +434,12 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   constexpr int WN = 4 / WM;
   constexpr int BM = WM * MT * 32;
   static_assert(WN * NT * 32 == BN, "tile must be 256 columns wide");
-  constexpr int A_STAGE = BM * BK * 2;
-  constexpr int STAGE = A_STAGE + B_STAGE;
-  constexpr int LA = BM / 64;  // A loads per lane per stage
-  constexpr int LB = 4;        // B loads per lane per stage
+  constexpr int A_BLOCK = a_block_bytes(BM);
+  constexpr int B_RING = b_ring_offset(BM);
+  constexpr int LA = BM / 64;  // A loads per lane per K step (one block)
+  constexpr int LB = 4;        // B loads per lane per K step (one stage)
   constexpr int LS = LA + LB;
+  constexpr int FPB = BM / 64; // 32-row fragments per A block
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   // The thread index is made opaque per tile: otherwise the lane-dependent address constants of all three tile
@@ -431,20 +453,22 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   const int row0 = uniform(cur.rec.row0), nrows = uniform(cur.rec.nrows), n_tile = uniform(cur.rec.n_tile);
   const int col0 = (MODE == MODE_L0_SWIGLU) ? n_tile * (BN / 2) : n_tile * BN;
 
-  // LDS read addresses (stage 0)
-  uint32_t a_rd[2], b_rd[NT];
+  // LDS read addresses: a_rd[parity of the K step][16-deep half of the step] inside an A block, b_rd inside a B stage
+  uint32_t a_rd[2][2], b_rd[NT];
   {
-    const int r = wm * (MT * 32) + (lane & 31);
-    const int s = (r >> 2) & 3;
+    const int l = lane & 31;
+    const int s = (l >> 1) & 7;
 #pragma unroll
-    for (int kk = 0; kk < 2; kk++) a_rd[kk] = lds0 + r * 64 + (((kk * 2 + (lane >> 5)) ^ s) << 4);
+    for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+      for (int kk = 0; kk < 2; kk++) a_rd[sub][kk] = lds0 + l * 128 + (((sub * 4 + kk * 2 + (lane >> 5)) ^ s) << 4);
     const int swz = (j16 >> 2) | ((g >> 1) << 2);
     const int krow = 8 * (g >> 1) + (j16 >> 2);
 #pragma unroll
     for (int nt = 0; nt < NT; nt++)
-      b_rd[nt] = lds0 + A_STAGE + krow * 512 + (((wn * NT + nt) ^ swz) << 6) + (16 * (g & 1) + 4 * (j16 & 3)) * 2;
+      b_rd[nt] = lds0 + B_RING + krow * 512 + (((wn * NT + nt) ^ swz) << 6) + (16 * (g & 1) + 4 * (j16 & 3)) * 2;
   }
-  // address set-up and the loads of the first NS-1 stages
+  // address set-up and the first loads (A blocks 0..2, B stages 0..2)
   LoadState ls;
   setup_and_issue<WM, MT, NT, MODE>(p, lds0, cur, ls, lane, w, !cur.pre);
   const char* Ab = uniform(ls.Ab);
@@ -457,22 +481,26 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int j = 0; j < NT; j++) acc[i][j] = (f32x16){0};
 
-  // One stage = LA loads of A rows and LB loads of B rows per lane.  The loads are issued one at a time between
-  // groups of MFMAs: a burst would fill the vector-memory queue and stall the MFMAs queued behind it.
-  auto issue_a = [&](int stage, int j) { dma16(Ab, ls.aoff[j], lds0 + stage * STAGE + (w * LA + j) * 1024); };
-  auto issue_b = [&](int stage, int j) { dma16(Bb, ls.boff[j], lds0 + stage * STAGE + A_STAGE + (w * LB + j) * 1024); };
-  auto advance = [&]() {
-    Ab += BK * 2;
-    Bb += bstep;
+  // Per K step and lane: LA loads of A (block kt+3: the other half of the rows than the block before, 64 values of K)
+  // and LB loads of B (stage kt+3).  The loads are issued one at a time between groups of MFMAs: a burst would fill
+  // the vector-memory queue and stall the MFMAs queued behind it.
+  using P0 = std::integral_constant<int, 0>;
+  using P1 = std::integral_constant<int, 1>;
+  // LDS offset of the A block that holds row half hh for K step `step`
+  auto a_slot = [&](int step, int hh) { return (uint32_t)((2 * (step >> 1) + hh) % kABlocks) * A_BLOCK; };
+  // where fragment q (32 rows) of this wavefront sits: row half and offset inside the block
+  auto frag_off = [&](const uint32_t (&blk)[2], int q) {
+    const int f = wm * MT + q;   // WM == 2: f / FPB == wm for every q
+    return (WM == 2 ? (wm ? blk[1] : blk[0]) : blk[f / FPB]) + (uint32_t)(f % FPB) * (32 * 128);
   };
   bf16x8 af[2][MT], bfr[2][NT];
   // Group q (of 4) of a half step: the LDS reads of fragment q for the next half step and a quarter of the MFMAs
-  // of this one.  rd_off / rd_kk: stage offset and 16-deep sub-step the fragments are read from.
-  auto group = [&](int cb, int nb, uint32_t rd_off, int rd_kk, int q) {
+  // of this one.  blk / b_off / rd_par / rd_kk: A blocks, B stage, parity and 16-deep half of the step read from.
+  auto group = [&](int cb, int nb, const uint32_t (&blk)[2], uint32_t b_off, int rd_par, int rd_kk, int q) {
     constexpr int PER = MT * NT / 4;
-    if (q < MT) af[nb][q] = lds_read_a(rd_off + a_rd[rd_kk] + q * 32 * 64);
+    if (q < MT) af[nb][q] = lds_read_a(frag_off(blk, q) + a_rd[rd_par][rd_kk]);
     if (q < NT)
-      bfr[nb][q] = lds_read_b(rd_off + b_rd[q] + rd_kk * 16 * 512, rd_off + b_rd[q] + (rd_kk * 16 + 4) * 512);
+      bfr[nb][q] = lds_read_b(b_off + b_rd[q] + rd_kk * 16 * 512, b_off + b_rd[q] + (rd_kk * 16 + 4) * 512);
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       const int m = q * PER + i, mt = m / NT, nt = m % NT;
@@ -488,18 +516,30 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     for (int i = PER; i < 3; i++)
       if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   };
-  auto half1 = [&](int stage_issue, bool do_issue, uint32_t so) {
+  // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+3
+  auto half1 = [&](auto par, int kt, bool do_issue) {
+    constexpr int PAR = decltype(par)::value;
+    const uint32_t blk[2] = {a_slot(kt, 0), a_slot(kt, 1)};
+    const uint32_t b_off = (uint32_t)(kt % NS) * B_STAGE;
+    const int b = kt + 3;
+    const char* src = Ab + (b >> 1) * 128;
+    const uint32_t dst = lds0 + (uint32_t)(b % kABlocks) * A_BLOCK + w * LA * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
-      if (do_issue && q < LA) issue_a(stage_issue, q);
-      group(0, 1, so, 1, q);
+      if (do_issue && q < LA) dma16(src, ls.aoff[(1 - PAR) * LA + q], dst + q * 1024);
+      group(0, 1, blk, b_off, PAR, 1, q);
     }
   };
-  auto half2 = [&](int stage_issue, bool do_issue, uint32_t sn) {
+  // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+3
+  auto half2 = [&](auto par, int kt, bool do_issue) {
+    constexpr int PAR = decltype(par)::value;
+    const uint32_t blk[2] = {a_slot(kt + 1, 0), a_slot(kt + 1, 1)};
+    const uint32_t b_off = (uint32_t)((kt + 1) % NS) * B_STAGE;
+    const uint32_t dst = lds0 + B_RING + (uint32_t)((kt + 3) % NS) * B_STAGE + w * LB * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
-      if (do_issue && q < LB) issue_b(stage_issue, q);
-      group(1, 0, sn, 0, q);
+      if (do_issue && q < LB) dma16(Bb, ls.boff[q], dst + q * 1024);
+      group(1, 0, blk, b_off, 1 - PAR, 0, q);
     }
   };
 
@@ -517,37 +557,44 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   if (kCanPre && flags_on && tid < p.n_segments)
     flag_v = __hip_atomic_load(&p.seg_ready[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 
-  const int nk = p.K / BK;  // >= NS - 1 (checked on the host)
-  // first stage landed?  Everything issued after it (two more stages, and whatever the previous tile's epilogue
-  // stored) may still be outstanding; loads return in order, so at most 2*LS outstanding means stage 0 is there.
-  wait_vmcnt<(NS - 2) * LS>();
+  const int nk = p.K / BK;  // even and >= 4 (checked on the host)
+  // A blocks 0 and 1 and B stage 0 landed?  Everything issued after them (A block 2, B stages 1 and 2, and whatever
+  // the previous tile's epilogue stored) may still be outstanding; loads return in order.
+  wait_vmcnt<LA + 2 * LB>();
   block_barrier();
+  {
+    const uint32_t blk[2] = {a_slot(0, 0), a_slot(0, 1)};
 #pragma unroll
-  for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(a_rd[0] + mt * 32 * 64);
+    for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(frag_off(blk, mt) + a_rd[0][0]);
+  }
 #pragma unroll
   for (int nt = 0; nt < NT; nt++) bfr[0][nt] = lds_read_b(b_rd[nt], b_rd[nt] + 4 * 512);
 
   int kt = 0;
-  auto steady = [&](int kt_end) {
-    for (; kt < kt_end; kt++) {
-      const int st = (kt + NS - 1) % NS;
-      half1(st, true, (kt % NS) * STAGE);
-      // stage kt+1 has landed for this lane (younger: stage kt+2 and the A rows of stage kt+3); after the barrier
-      // it has for all, and all are done reading stage kt
-      wait_vmcnt<LS + LA>();
-      block_barrier();
-      half2(st, true, ((kt + 1) % NS) * STAGE);
-      advance();
-    }
+  auto step = [&](auto par) {
+    half1(par, kt, true);
+    // B stage kt+1 and the A blocks of step kt+1 have landed for this lane (younger: B stage kt+2 and A block kt+3);
+    // after the barrier they have for all, and all are done reading step kt
+    wait_vmcnt<LS>();
+    block_barrier();
+    half2(par, kt, true);
+    Bb += bstep;
+    kt++;
   };
-  steady(nk - (NS - 1));
+  const int kt_end = nk - (NS - 1);   // odd
+  while (kt + 2 <= kt_end) {
+    step(P0{});
+    step(P1{});
+  }
+  if (kt < kt_end) step(P0{});
 
-  half1(0, false, (kt % NS) * STAGE);
-  wait_vmcnt<LS>();
+  // the last three steps (parities 1, 0, 1) issue nothing
+  half1(P1{}, kt, false);
+  wait_vmcnt<LB>();   // younger than the last A block: the last B stage
   block_barrier();
-  half2(0, false, ((kt + 1) % NS) * STAGE);
+  half2(P1{}, kt, false);
   kt++;
-  half1(0, false, (kt % NS) * STAGE);
+  half1(P0{}, kt, false);
   wait_vmcnt<0>();
   // No operand load is in flight any more, so memory operations the compiler waits for by itself no longer stall
   // behind them: thread 0 turns its queue ticket into a list position (stealing from other XCDs if its own queue is
@@ -569,9 +616,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     ready_mask = (uint32_t)uniform((int)lds_mask[0]) | ((uint64_t)(uint32_t)uniform((int)lds_mask[1]) << 32);
   ItemRec raw_rec;
   if (next.idx >= 0) raw_rec = p.items[next.idx];
-  half2(0, false, ((kt + 1) % NS) * STAGE);
+  half2(P0{}, kt, false);
   kt++;
-  half1(0, false, (kt % NS) * STAGE);
+  half1(P1{}, kt, false);
 #pragma unroll
   for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -587,8 +634,8 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   block_barrier();   // every wavefront is done reading the operand stages
 
   if (next.idx >= 0) next.rec = make_uniform(raw_rec);
-  // early start of the successor (see above): its gather rows are requested now, its first stages after the first
-  // 32-row block of the epilogue, into the three stages the epilogue does not use
+  // early start of the successor (see above): its gather rows are requested now, its first loads after the first
+  // 32-row block of the epilogue, into LDS the epilogue does not use
   bool do_pre = false;
   if (kCanPre && next.idx >= 0 && next.rec.kind == kKind && ((ready_mask >> (next.rec.ready_seg & 63)) & 1)) do_pre = true;
   next.pre = do_pre;
@@ -611,7 +658,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   constexpr int NST = 32 * PNC / 64;                                // 16-byte stores per lane and piece
   constexpr int NPIECE = MT * PH;
   static_assert(OUT_NT % PW == 0, "pieces tile the wavefront's columns");
-  const uint32_t cbase = lds0 + kStagingOffset + w * (2 * 32 * PRB);   // 2 buffers x 32 rows x 128 bytes per wavefront
+  const uint32_t cbase = lds0 + staging_offset(BM) + w * (2 * 32 * PRB);   // 2 buffers x 32 rows x 128 bytes per wavefront
   int lane_e = lane;   // opaque again: the epilogue's addresses are computed here, not before the main loop
   asm volatile("" : "+v"(lane_e));
   const int col_base = (MODE == MODE_L0_SWIGLU) ? col0 + wn * (NT * 16) : col0 + wn * (NT * 32);
@@ -760,7 +807,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
 
 template <int MODE>
 static hipError_t launch_gemm(const GemmParams& p, int grid, hipStream_t st) {
-  constexpr int lds = NS * (256 * BK * 2 + B_STAGE);
+  constexpr int lds = kLdsBytes;
   auto kern = k_group_gemm<MODE>;
   static bool attr_set = false;
   if (!attr_set) {
