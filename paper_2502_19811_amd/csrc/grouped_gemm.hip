@@ -751,7 +751,6 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     if (p.fused_combine) combine_loop(p, &lds_slot[1], false);
     return;
   }
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int xcd = blockIdx.x & (kXcds - 1);
   Queue q;
