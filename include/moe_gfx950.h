@@ -170,8 +170,9 @@ int moe_probe_mfma(int32_t random_data, int32_t iters, void *scratch, size_t scr
                    void *hip_stream);
 int moe_probe_copy(void *dst, const void *src, size_t bytes, float *gbytes_per_s, void *hip_stream);
 
-/* Status word written by the kernels of the last forward (0, or MOE_ERR_TIMEOUT when a bounded
- * flag wait expired).  Synchronises the stream. */
+/* What the kernels of the last forward reported: 0, MOE_ERR_TIMEOUT when a bounded flag wait expired, or
+ * MOE_ERR_INVALID_ARG when topk_ids held a value outside [0, E) (such a pair is routed to the last expert, so that
+ * nothing is accessed out of bounds; the output rows of its token are then meaningless).  Synchronises the stream. */
 int moe_last_device_status(const moe_plan_t *plan, const void *workspace, void *hip_stream);
 
 const char *moe_status_string(int status);

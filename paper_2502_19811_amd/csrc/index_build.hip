@@ -74,7 +74,14 @@ __global__ __launch_bounds__(256) void k_index_hist(IndexParams p) {
 #pragma unroll
   for (int i = 0; i < kIndexChunk / 256; i++) {
     int q = base + i * 256 + threadIdx.x;
-    if (q < R) atomicAdd(&hist[p.topk_ids[q]], 1);
+    if (q < R) {
+      int e = p.topk_ids[q];
+      if ((unsigned)e >= (unsigned)E) {   // not an expert: reported through the status word, counted as the last expert
+        p.ws.status[5] = p.forward_serial;
+        e = E - 1;
+      }
+      atomicAdd(&hist[e], 1);
+    }
   }
   __syncthreads();
   for (int e = threadIdx.x; e < E; e += 256) p.ws.block_hist[blockIdx.x * E + e] = hist[e];
@@ -210,7 +217,8 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
     const int run = wave * (kRuns / 4) + s;
     const int q = base + run * 64 + lane;
     const bool valid = q < R;
-    const int e = valid ? p.topk_ids[q] : -1;
+    int e = valid ? p.topk_ids[q] : -1;
+    if (valid && (unsigned)e >= (unsigned)E) e = E - 1;   // as in the histogram
     // lanes of this run holding the same expert
     uint64_t same = __ballot(valid);
 #pragma unroll

@@ -29,6 +29,7 @@ struct moe_plan {
   int32_t max_tiles;
   int32_t large_schedule;  // 1: always the one-workgroup schedule builder
   int32_t block_m;         // M-tiles per block of the locality order
+  int32_t serial;          // number of the last forward (tags the out-of-range report in the status words)
   int32_t n_tiles_n0, n_tiles_n1;
   size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
       off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_h, off_Y, total_bytes;
@@ -144,6 +145,7 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
   p->n_dm = -1;
   p->layer0_order = 0;
   p->layer1_order = 0;   // measured faster on every workload so far: see the sweep tool and default_n_dm
+  p->serial = 0x2545F491;   // arbitrary start: an uninitialised workspace word is unlikely to match it
   p->block_m = 4;        // measured: 2-4 % faster on layer1 than 8, see the header
   p->spin_limit = 0;
   p->phases = 15;
@@ -293,6 +295,7 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     ip.max_tiles = p->max_tiles;
     ip.force_large_schedule = p->large_schedule;
     ip.block_m = p->block_m;
+    ip.forward_serial = ++p->serial;
     memcpy(ip.seg_offsets, p->seg_offsets, sizeof(int32_t) * (s.S + 1));
     if (launch_index_build(ip, st) != hipSuccess) return MOE_ERR_HIP;
   }
@@ -481,10 +484,11 @@ int moe_play_arrival(const moe_plan_t* p, const void* staging, void* x, uint32_t
 int moe_last_device_status(const moe_plan_t* p, const void* workspace, void* hip_stream) {
   if (!p || !workspace) return MOE_ERR_INVALID_ARG;
   Workspace ws = view(p, const_cast<void*>(workspace));
-  int32_t v = 0;
-  if (hipMemcpyAsync(&v, ws.status, 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream) != hipSuccess) return MOE_ERR_HIP;
+  int32_t v[6] = {0, 0, 0, 0, 0, 0};
+  if (hipMemcpyAsync(v, ws.status, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)hip_stream) != hipSuccess) return MOE_ERR_HIP;
   if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return MOE_ERR_HIP;
-  return v;
+  if (v[0] != 0) return v[0];
+  return v[5] == p->serial ? MOE_ERR_INVALID_ARG : MOE_OK;
 }
 
 const char* moe_status_string(int status) {

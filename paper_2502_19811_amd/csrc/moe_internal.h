@@ -30,7 +30,8 @@ struct ItemRec {
 // Device-side view of the workspace (all pointers into the caller's workspace buffer).
 struct Workspace {
   int32_t* status;        // [64]  0: device status word, 1: n_tiles, 2: items of layer0, 3: items of layer1,
-                          //       4: combine unit counter; per XCD: 8..15 layer0 queue heads, 16..23 layer1 queue
+                          //       4: combine unit counter, 5: serial number of the last forward that saw an expert
+                          //       id out of range; per XCD: 8..15 layer0 queue heads, 16..23 layer1 queue
                           //       heads, 24..31 layer0 queue lengths, 32..39 layer1 queue lengths, 40..47 layer1
                           //       queue bases, 48..55 layer0 queue bases (only with contiguous layer0 queues;
                           //       otherwise layer0's queue x is list positions x, x+8, ...)
@@ -69,6 +70,7 @@ struct IndexParams {
   int32_t max_tiles;             // bound on the M-tiles of this plan
   int32_t force_large_schedule;  // 1: build the schedules with the one-workgroup kernel whatever the size
   int32_t block_m;               // M-tiles per block of the locality order (1..8)
+  int32_t forward_serial;        // written to status[5] when an expert id is out of range
   int32_t seg_offsets[kMaxSegments + 1];
 };
 

@@ -181,3 +181,28 @@ def test_one_plan_and_workspace_serve_different_routings_in_a_row():
     np.testing.assert_array_equal(third.perm, first.perm)
     a, b = H.error_metrics(third.out, ref1)
     assert a <= H.REL_TOL and b <= H.REL_TOL
+
+
+def test_expert_ids_out_of_range_are_reported_and_harmless():
+    """Ids outside [0, E) neither fault nor disturb other tokens: the forward reports them through the status word."""
+    import paper_2502_19811_amd as moe
+    H, cfg, inp, ids, w, layer = _setup()
+    bad = ids.copy()
+    bad_tokens = [3, 500, cfg.T - 1]
+    bad[3, 0] = -1
+    bad[500, 1] = cfg.E
+    bad[cfg.T - 1, 0] = 1 << 20
+    layer.ids.copy_(torch.from_numpy(bad).cuda())
+    layer.forward()
+    run = layer.results()
+    assert run.status == -1 and moe.moe_status_string(run.status) == "invalid argument"
+    assert int(run.counts.sum()) == cfg.R                       # every pair was routed somewhere
+    good = np.setdiff1d(np.arange(cfg.T), bad_tokens)
+    ref = orc.moe_layer_tokens(good, inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    a, b = H.error_metrics(run.out[good], ref)
+    assert a <= H.REL_TOL and b <= H.REL_TOL
+    # the next forward with valid ids reports nothing
+    layer.ids.copy_(torch.from_numpy(ids).cuda())
+    layer.forward()
+    assert layer.results().status == 0
+    layer.close()
