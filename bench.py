@@ -29,6 +29,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mixtral", help="tiny | mixtral | qwen2 | phi35 | skewed")
     ap.add_argument("--opt", action="append", default=[], help="plan option key=value (repeatable)")
+    ap.add_argument("--packed", type=int, default=0, choices=[0, 1],
+                    help="1: the weights are re-laid out once, before the timed steps, with moe_pack_weights")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
                     help="tokens the CPU oracle is timed (and the GPU output checked) on; 8192 is the whole default workload")
@@ -67,6 +69,13 @@ def main() -> int:
     for kv in args.opt:
         key, val = kv.split("=")
         moe.moe_plan_set_option(plan, key, int(val))
+    if args.packed:
+        W1p, W2p = torch.empty_like(W1), torch.empty_like(W2)
+        moe.moe_pack_weights(plan, W1, W2, W1p, W2p)
+        torch.cuda.synchronize()
+        W1, W2 = W1p, W2p
+        del W1p, W2p
+        moe.moe_plan_set_option(plan, "weights_packed", 1)
     ws = torch.zeros(moe.moe_plan_workspace_bytes(plan), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
 
@@ -134,6 +143,7 @@ def main() -> int:
                                f"{'SwiGLU' if cfg.act == wl.ACT_SWIGLU else 'GELU'} S={cfg.S} seed={cfg.seed}",
                    "tile_m": moe.moe_plan_get_option(plan, "tile_m"), "n_dm": moe.moe_plan_get_option(plan, "n_dm"),
                    "layer1_order": moe.moe_plan_get_option(plan, "layer1_order"),
+                   "weights_packed": moe.moe_plan_get_option(plan, "weights_packed"),
                    "gather": "fused into layer0's operand loads (no separate phase, no materialised copy)",
                    "device": device_info(torch),
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},

@@ -81,6 +81,8 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  one XCD (default 4: the 32 workgroups of an XCD then work on 4 M-tiles x 8 column tiles, and
  *                  two XCDs sweep the same weight panels of an expert with 8 M-tiles at the same time, the second
  *                  finding them in the Infinity Cache)
+ *   "weights_packed" 1: the W1 / W2 arguments of moe_layer_forward are buffers written by moe_pack_weights
+ *                  (default 0: the plain row-major weights)
  *   "large_schedule" 1: build the tile schedules with the one-workgroup kernel that has no limit on the
  *                  number of M-tiles (the default picks it only above 2048 tiles); its orders are simpler
  *                  (less operand sharing inside an XCD), the results are the same bit for bit
@@ -121,6 +123,18 @@ int moe_route_topk(const float *logits, int32_t T, int32_t E, int32_t k, int32_t
 int moe_layer_forward(moe_plan_t *plan, const void *x, const int32_t *topk_ids, const float *topk_weights,
                       const void *W1, const void *W2, int32_t act, void *out, void *workspace,
                       size_t workspace_bytes, const uint32_t *seg_ready, uint32_t ready_epoch, void *hip_stream);
+
+/* Plan-time re-layout of the expert weights for the GroupGEMM's operand path (Section 4: the GEMM operand pipeline;
+ * Section 3.2.2: whatever is decided per shape is prepared before launch).  W1 [E,H,F1] and W2 [E,F,H] (dev bf16,
+ * row-major as moe_layer_forward takes them) are rewritten into W1_packed / W2_packed (dev, same number of bytes
+ * as the source, 16-byte aligned, must not overlap it): per expert, column tile of 256 and step of 32 along the
+ * reduction, one contiguous 16 KiB block that is the LDS image of that operand stage in the matrix-core operand
+ * order, the blocks of a tile following each other.  For SwiGLU the gate and up columns of the same 128 hidden units
+ * share a tile.  A forward takes the packed buffers in place of W1 / W2 once the plan option "weights_packed" is 1;
+ * its results are the same bit for bit.  Either pair may be NULL (both pointers).  Enqueues on the stream; allocates
+ * nothing.  Needs to be repeated only when the weights change. */
+int moe_pack_weights(const moe_plan_t *plan, const void *W1, const void *W2, void *W1_packed, void *W2_packed,
+                     void *hip_stream);
 
 /* Copies the index outputs of the last forward on this workspace into caller memory (dev pointers;
  * enqueued on the stream; any of the four may be NULL):

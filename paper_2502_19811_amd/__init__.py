@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     moe_get_tile_table,
     moe_last_device_status,
     moe_layer_forward,
+    moe_pack_weights,
     moe_plan_create,
     moe_plan_destroy,
     moe_plan_get_option,

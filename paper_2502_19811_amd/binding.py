@@ -20,7 +20,7 @@ EXPORTS = [
     "moe_plan_workspace_bytes", "moe_plan_max_tiles", "moe_receive_buffer_bytes", "moe_route_topk",
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
     "moe_status_string", "moe_plan_phase_times", "moe_plan_forward_times", "moe_play_arrival",
-    "moe_probe_mfma", "moe_probe_copy",
+    "moe_probe_mfma", "moe_probe_copy", "moe_pack_weights",
 ]
 
 
@@ -85,6 +85,8 @@ def load_library():
     lib.moe_probe_copy.restype = C.c_int
     lib.moe_play_arrival.argtypes = [C.c_void_p, vp, vp, u32p, u32p, C.c_uint32, C.c_double, C.c_int32, vp]
     lib.moe_play_arrival.restype = C.c_int
+    lib.moe_pack_weights.argtypes = [C.c_void_p, vp, vp, vp, vp, vp]
+    lib.moe_pack_weights.restype = C.c_int
     lib.moe_status_string.argtypes = [C.c_int]
     lib.moe_status_string.restype = C.c_char_p
     _lib = lib
@@ -158,6 +160,11 @@ def moe_layer_forward(plan: int, x, topk_ids, topk_weights, W1, W2, act: int, ou
     _check(load_library().moe_layer_forward(plan, _ptr(x), _ptr(topk_ids), _ptr(topk_weights), _ptr(W1), _ptr(W2), act,
                                             _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _ptr(seg_ready), ready_epoch, _stream(stream)), "moe_layer_forward")
+
+
+def moe_pack_weights(plan: int, W1, W2, W1_packed, W2_packed, stream=None) -> None:
+    _check(load_library().moe_pack_weights(plan, _ptr(W1), _ptr(W2), _ptr(W1_packed), _ptr(W2_packed), _stream(stream)),
+           "moe_pack_weights")
 
 
 def moe_get_index_outputs(plan: int, workspace, expert_counts=None, expert_offsets=None, perm=None, inv_perm=None,

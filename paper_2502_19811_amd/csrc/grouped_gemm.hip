@@ -31,6 +31,11 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 enum { MODE_L0_GELU = 0, MODE_L0_SWIGLU = 1, MODE_L1 = 2 };
 
 constexpr int BK = kTileK, NS = kStages, BN = kTileN;
+#ifndef MOE_READ_GROUPS
+#define MOE_READ_GROUPS 2
+#endif
+constexpr int kReadGroups = MOE_READ_GROUPS;        // of the 4 groups of a half step, how many carry the LDS reads
+constexpr int kFragsPerGroup = 4 / kReadGroups;     // fragments (of at most 4 per operand) requested per such group
 constexpr int kMaxPanels = 128;   // column panels whose publication can be batched per workgroup
 constexpr int B_STAGE = BK * BN * 2;  // 16 KiB
 
@@ -43,6 +48,10 @@ __device__ __forceinline__ bf16x8 lds_read_b(uint32_t a0, uint32_t a1) {
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(uintptr_t)a1);
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
+}
+// Packed weights: a fragment (32 columns x 16 values of K) lies in LDS in lane order, 16 bytes per lane.
+__device__ __forceinline__ bf16x8 lds_read_b_packed(uint32_t a) {
+  return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a;
 }
 // 16 bytes per lane from sbase + voff straight into LDS at lds_base + lane * 16.  Written as asm so that the
 // compiler's wait-count pass does not serialise later LDS reads behind it; completion is awaited by hand
@@ -345,7 +354,7 @@ __device__ __forceinline__ void load_arows(const GemmParams& p, Tile& t, int lan
 // A: lane l of a load fetches the 16 bytes at position (l & 7) ^ ((row / 2) & 7) of its row's 128-byte line, so that
 // the line lands in LDS (linearly, 16 bytes per lane) with its chunks XOR-swizzled by row: the 16 rows one pass of
 // ds_read_b128 touches then fall on distinct banks.
-template <int WM, int MT, int NT, int MODE>
+template <int WM, int MT, int NT, int MODE, bool PK>
 __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t lds0, const Tile& t, LoadState& ls, int lane,
                                                 int w, bool issue) {
   constexpr int BM = WM * MT * 32;
@@ -361,6 +370,11 @@ __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t ld
   const int col0 = (MODE == MODE_L0_SWIGLU) ? t.rec.n_tile * (BN / 2) : t.rec.n_tile * BN;
 #pragma unroll
   for (int j = 0; j < LB; j++) {
+    if (PK) {
+      // packed weights: a stage is 16 KiB in a row, already in its LDS order
+      ls.boff[j] = (uint32_t)((w * LB + j) * 1024 + lane * 16);
+      continue;
+    }
     const int kr = (w * LB + j) * 2 + (lane >> 5);
     const int cpb = lane & 31;
     const int blk = (cpb >> 2) ^ ((kr & 3) | (((kr >> 3) & 1) << 2));
@@ -377,8 +391,9 @@ __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t ld
     ls.boff[j] = ((uint32_t)kr * p.ldb + gcol) * 2;
   }
   ls.Ab = uniform(p.A);
-  ls.Bb = uniform(p.B + (uint64_t)t.rec.expert * p.b_expert_bytes);
-  const size_t bstep = (size_t)BK * p.ldb * 2;
+  ls.Bb = PK ? uniform(p.B + ((uint64_t)t.rec.expert * p.n_tiles_n + t.rec.n_tile) * ((uint64_t)(p.K / BK) * B_STAGE))
+             : uniform(p.B + (uint64_t)t.rec.expert * p.b_expert_bytes);
+  const size_t bstep = PK ? (size_t)B_STAGE : (size_t)BK * p.ldb * 2;
   if (issue) {
     auto a_block = [&](int b) {
 #pragma unroll
@@ -427,7 +442,7 @@ __device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t
 // through LDS and the item record is requested.  A tile followed by one of the same height also starts the
 // successor's first operand stages during its own epilogue (next.pre = 1); otherwise only the rows of A the next
 // tile gathers are requested, after the epilogue.  next.idx = -1: no further tile.
-template <int WM, int MT, int NT, int MODE>
+template <int WM, int MT, int NT, int MODE, bool PK>
 __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, const Tile& cur,
                                          Tile& next, int xcd, const Queue& q, int& pending_panel,
                                          volatile int32_t* lds_panel_count_ptr, volatile uint32_t* lds_mask) {
@@ -465,15 +480,23 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const int swz = (j16 >> 2) | ((g >> 1) << 2);
     const int krow = 8 * (g >> 1) + (j16 >> 2);
 #pragma unroll
-    for (int nt = 0; nt < NT; nt++)
-      b_rd[nt] = lds0 + B_RING + krow * 512 + (((wn * NT + nt) ^ swz) << 6) + (16 * (g & 1) + 4 * (j16 & 3)) * 2;
+    for (int nt = 0; nt < NT; nt++) {
+      if (PK) {
+        // column block of the packed tile this wavefront's block nt is: SwiGLU tiles hold [4 gate | 4 up] blocks of the
+        // same 128 hidden units, of which a wavefront takes the gate and up blocks of its own units
+        const int c = MODE == MODE_L0_SWIGLU ? (nt / (NT / 2)) * 4 + wn * (NT / 2) + nt % (NT / 2) : wn * NT + nt;
+        b_rd[nt] = lds0 + B_RING + c * 1024 + lane * 16;
+      } else {
+        b_rd[nt] = lds0 + B_RING + krow * 512 + (((wn * NT + nt) ^ swz) << 6) + (16 * (g & 1) + 4 * (j16 & 3)) * 2;
+      }
+    }
   }
   // address set-up and the first loads (A blocks 0..2, B stages 0..2)
   LoadState ls;
-  setup_and_issue<WM, MT, NT, MODE>(p, lds0, cur, ls, lane, w, !cur.pre);
+  setup_and_issue<WM, MT, NT, MODE, PK>(p, lds0, cur, ls, lane, w, !cur.pre);
   const char* Ab = uniform(ls.Ab);
   const char* Bb = uniform(ls.Bb);
-  const size_t bstep = (size_t)BK * p.ldb * 2;
+  const size_t bstep = PK ? (size_t)B_STAGE : (size_t)BK * p.ldb * 2;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -498,22 +521,34 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // of this one.  blk / b_off / rd_par / rd_kk: A blocks, B stage, parity and 16-deep half of the step read from.
   auto group = [&](int cb, int nb, const uint32_t (&blk)[2], uint32_t b_off, int rd_par, int rd_kk, int q) {
     constexpr int PER = MT * NT / 4;
-    if (q < MT) af[nb][q] = lds_read_a(frag_off(blk, q) + a_rd[rd_par][rd_kk]);
-    if (q < NT)
-      bfr[nb][q] = lds_read_b(b_off + b_rd[q] + rd_kk * 16 * 512, b_off + b_rd[q] + (rd_kk * 16 + 4) * 512);
+    // The fragments of the next half step are all requested in the first kReadGroups groups, so that they are back
+    // well before the half step ends: the workgroup barrier between the halves waits for every outstanding LDS
+    // read, and a read issued just before it would stall all four matrix pipes for an LDS round trip.
+    int n_reads = 0;
+#pragma unroll
+    for (int f = q * kFragsPerGroup; f < (q + 1) * kFragsPerGroup; f++) {
+      if (q < kReadGroups && f < MT) {
+        af[nb][f] = lds_read_a(frag_off(blk, f) + a_rd[rd_par][rd_kk]);
+        n_reads += 1;
+      }
+      if (q < kReadGroups && f < NT) {
+        if (PK) bfr[nb][f] = lds_read_b_packed(b_off + b_rd[f] + rd_kk * (B_STAGE / 2));
+        else bfr[nb][f] = lds_read_b(b_off + b_rd[f] + rd_kk * 16 * 512, b_off + b_rd[f] + (rd_kk * 16 + 4) * 512);
+        n_reads += PK ? 1 : 2;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       const int m = q * PER + i, mt = m / NT, nt = m % NT;
       acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][nt], af[cb][mt], acc[mt][nt], 0, 0, 0);
     }
-    const int n_reads = (q < MT ? 1 : 0) + (q < NT ? 2 : 0);
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
 #pragma unroll
-    for (int i = PER; i < 3; i++)
+    for (int i = PER; i < 12; i++)
       if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   };
   // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+3
@@ -526,6 +561,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const uint32_t dst = lds0 + (uint32_t)(b % kABlocks) * A_BLOCK + w * LA * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
+      if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
       if (do_issue && q < LA) dma16(src, ls.aoff[(1 - PAR) * LA + q], dst + q * 1024);
       group(0, 1, blk, b_off, PAR, 1, q);
     }
@@ -538,6 +574,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const uint32_t dst = lds0 + B_RING + (uint32_t)((kt + 3) % NS) * B_STAGE + w * LB * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
+      if (q > 0) __builtin_amdgcn_sched_barrier(0);
       if (do_issue && q < LB) dma16(Bb, ls.boff[q], dst + q * 1024);
       group(1, 0, blk, b_off, 1 - PAR, 0, q);
     }
@@ -568,15 +605,18 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(frag_off(blk, mt) + a_rd[0][0]);
   }
 #pragma unroll
-  for (int nt = 0; nt < NT; nt++) bfr[0][nt] = lds_read_b(b_rd[nt], b_rd[nt] + 4 * 512);
+  for (int nt = 0; nt < NT; nt++) bfr[0][nt] = PK ? lds_read_b_packed(b_rd[nt]) : lds_read_b(b_rd[nt], b_rd[nt] + 4 * 512);
 
   int kt = 0;
   auto step = [&](auto par) {
     half1(par, kt, true);
     // B stage kt+1 and the A blocks of step kt+1 have landed for this lane (younger: B stage kt+2 and A block kt+3);
-    // after the barrier they have for all, and all are done reading step kt
+    // after the barrier they have for all, and all are done reading step kt.  The scheduler must not move MFMAs of the
+    // first half behind the barrier: they are what covers the latency of the half's LDS reads before the wait.
+    __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<LS>();
     block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     half2(par, kt, true);
     Bb += bstep;
     kt++;
@@ -722,7 +762,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       if (s == PH && do_pre) {   // the first 32-row block is out
         if (flags_on) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
         LoadState ls_next;
-        setup_and_issue<WM, MT, NT, MODE>(p, lds0, next, ls_next, lane_e, w, true);
+        setup_and_issue<WM, MT, NT, MODE, PK>(p, lds0, next, ls_next, lane_e, w, true);
       }
     }
   }
@@ -737,7 +777,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   if (next.idx >= 0 && !do_pre) load_arows<MODE>(p, next, lane, w);
 }
 
-template <int MODE>
+template <int MODE, bool PK>
 __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int32_t lds_slot[2];
@@ -784,9 +824,9 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
       continue;
     }
     next.idx = -1;
-    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
-    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
-    else run_tile<1, 2, 2, MODE>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+    if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE, PK>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+    else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE, PK>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+    else run_tile<1, 2, 2, MODE, PK>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
     cur = next;
   }
   if (MODE == MODE_L1 && p.fused_combine) {
@@ -804,26 +844,71 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   }
 }
 
-template <int MODE>
+template <int MODE, bool PK>
 static hipError_t launch_gemm(const GemmParams& p, int grid, hipStream_t st) {
   constexpr int lds = kLdsBytes;
-  auto kern = k_group_gemm<MODE>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  auto kern = k_group_gemm<MODE, PK>;
+  // The kernel needs more dynamic LDS than the default limit.  The attribute belongs to the function on the current
+  // device, so it is set on every launch (a host-side table look-up, no device work): a cached "done" flag would be
+  // wrong on a second device and racy between threads.
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);
   return hipGetLastError();
 }
 
 hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st) {
-  if (act == MOE_ACT_SWIGLU) return launch_gemm<MODE_L0_SWIGLU>(p, grid, st);
-  return launch_gemm<MODE_L0_GELU>(p, grid, st);
+  if (act == MOE_ACT_SWIGLU) return p.b_packed ? launch_gemm<MODE_L0_SWIGLU, true>(p, grid, st) : launch_gemm<MODE_L0_SWIGLU, false>(p, grid, st);
+  return p.b_packed ? launch_gemm<MODE_L0_GELU, true>(p, grid, st) : launch_gemm<MODE_L0_GELU, false>(p, grid, st);
 }
 
-hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st) { return launch_gemm<MODE_L1>(p, grid, st); }
+hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st) {
+  return p.b_packed ? launch_gemm<MODE_L1, true>(p, grid, st) : launch_gemm<MODE_L1, false>(p, grid, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight packing (once per set of weights, outside the forward): B [E][K][ldb] row-major becomes, per expert, column
+// tile and K step of 32, the 16 KiB LDS image of that stage: 16 fragments of 1 KiB, fragment (kk, c) = 16 values of K
+// (kk-th half of the step) x 32 columns (c-th block of the tile), lane l of a wavefront owning the 8 K-consecutive
+// values k = kk*16 + (l/32)*8 .. +7 of column l%32 -- the operand layout of v_mfma_f32_32x32x16_bf16.  A tile's stages
+// follow each other in memory, so a workgroup streams one contiguous run per tile.
+// Column blocks: plain layers, block c = columns [32c, 32c+32) of the tile.  SwiGLU W1 ([gate | up] column halves): tile
+// n covers hidden units [128n, 128n+128); blocks 0..3 are their gate columns, blocks 4..7 their up columns.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pack_weights(const uint16_t* __restrict__ B, uint16_t* __restrict__ out, int K, int ldb,
+                                                      int n_tiles_n, int swiglu_F, size_t total_chunks) {
+  // one 16-byte chunk (8 values of K for one column) per thread step
+  const int nk = K / BK;
+  for (size_t ch = (size_t)blockIdx.x * 256 + threadIdx.x; ch < total_chunks; ch += (size_t)gridDim.x * 256) {
+    const int l = (int)(ch & 63);
+    const int frag = (int)((ch >> 6) & 15);
+    const size_t stage = ch >> 10;
+    const int kt = (int)(stage % nk);
+    const size_t en = stage / nk;
+    const int n = (int)(en % n_tiles_n);
+    const size_t e = en / n_tiles_n;
+    const int kk = frag >> 3, c = frag & 7;
+    const int k0 = kt * BK + kk * 16 + (l >> 5) * 8;
+    int col;
+    if (swiglu_F > 0) col = (c >> 2) * swiglu_F + n * (BN / 2) + (c & 3) * 32 + (l & 31);
+    else col = n * BN + c * 32 + (l & 31);
+    const uint16_t* src = B + (e * K + k0) * (size_t)ldb + col;
+    u32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; i++) v[i] = (uint32_t)src[(size_t)(2 * i) * ldb] | ((uint32_t)src[(size_t)(2 * i + 1) * ldb] << 16);
+    *(u32x4*)(out + ch * 8) = v;
+  }
+}
+
+hipError_t launch_pack_weights(const void* B, void* out, int E, int K, int ldb, int n_tiles_n, int swiglu_F, hipStream_t st) {
+  const size_t total_chunks = (size_t)E * n_tiles_n * (K / BK) * (B_STAGE / 16);
+  if (total_chunks == 0) return hipSuccess;
+  size_t grid = (total_chunks + 255) / 256;
+  if (grid > 256 * 32) grid = 256 * 32;
+  hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)grid), dim3(256), 0, st, (const uint16_t*)B, (uint16_t*)out, K, ldb, n_tiles_n,
+                     swiglu_F, total_chunks);
+  return hipGetLastError();
+}
 
 // ---------------------------------------------------------------------------------------------
 // Stand-alone top-k weighted reduction (used when the layer1 kernel runs without data-movement workgroups).

@@ -29,6 +29,7 @@ struct moe_plan {
   int32_t max_tiles;
   int32_t large_schedule;  // 1: always the one-workgroup schedule builder
   int32_t block_m;         // M-tiles per block of the locality order
+  int32_t weights_packed;  // 1: W1 / W2 of a forward are in the layout moe_pack_weights writes
   int32_t serial;          // number of the last forward (tags the out-of-range report in the status words)
   int32_t n_tiles_n0, n_tiles_n1;
   size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
@@ -211,6 +212,11 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     p->large_schedule = (int32_t)v;
     return MOE_OK;
   }
+  if (!strcmp(key, "weights_packed")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->weights_packed = (int32_t)v;
+    return MOE_OK;
+  }
   if (!strcmp(key, "profile")) {
     if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
     if (v == 1 && !p->ev_created) {
@@ -238,6 +244,7 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   else if (!strcmp(key, "profile")) *v = p->profile;
   else if (!strcmp(key, "large_schedule")) *v = p->large_schedule;
   else if (!strcmp(key, "block_m")) *v = p->block_m;
+  else if (!strcmp(key, "weights_packed")) *v = p->weights_packed;
   else return MOE_ERR_INVALID_ARG;
   return MOE_OK;
 }
@@ -325,6 +332,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     a.B = (const char*)W1;
     a.b_expert_bytes = (uint64_t)s.H * s.F1 * 2;
     a.ldb = (uint32_t)s.F1;
+    a.b_packed = p->weights_packed;
+    a.n_tiles_n = p->n_tiles_n0;
     a.C = ws.h;
     a.ldc = (uint32_t)s.F;
     a.K = s.H;
@@ -359,6 +368,8 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
     b.B = (const char*)W2;
     b.b_expert_bytes = (uint64_t)s.F * s.H * 2;
     b.ldb = (uint32_t)s.H;
+    b.b_packed = p->weights_packed;
+    b.n_tiles_n = p->n_tiles_n1;
     b.C = ws.Y;
     b.ldc = (uint32_t)s.H;
     b.K = s.F;
@@ -396,6 +407,19 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
   }
   if (!mark(4)) return MOE_ERR_HIP;
   if (ev) p->prof_steps++;
+  return MOE_OK;
+}
+
+int moe_pack_weights(const moe_plan_t* p, const void* W1, const void* W2, void* W1_packed, void* W2_packed, void* hip_stream) {
+  if (!p || (!W1 != !W1_packed) || (!W2 != !W2_packed)) return MOE_ERR_INVALID_ARG;
+  if ((W1 && (!aligned16(W1) || !aligned16(W1_packed) || W1 == W1_packed)) ||
+      (W2 && (!aligned16(W2) || !aligned16(W2_packed) || W2 == W2_packed)))
+    return MOE_ERR_INVALID_ARG;
+  const Shape& s = p->s;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (W1 && launch_pack_weights(W1, W1_packed, s.E, s.H, s.F1, p->n_tiles_n0, s.act == MOE_ACT_SWIGLU ? s.F : 0, st) != hipSuccess)
+    return MOE_ERR_HIP;
+  if (W2 && launch_pack_weights(W2, W2_packed, s.E, s.F, s.H, p->n_tiles_n1, 0, st) != hipSuccess) return MOE_ERR_HIP;
   return MOE_OK;
 }
 

@@ -81,6 +81,8 @@ struct GemmParams {
   const char* B;            // W1 or W2
   uint64_t b_expert_bytes;  // bytes between experts
   uint32_t ldb;             // elements per row of B
+  int32_t b_packed;         // 1: B is in the packed layout of moe_pack_weights (b_expert_bytes and ldb unused)
+  int32_t n_tiles_n;        // column tiles of this layer (addressing of packed B)
   uint16_t* C;              // h (layer0) or Y (layer1)
   uint32_t ldc;             // elements per row of C
   int32_t K;                // reduction length
@@ -139,6 +141,7 @@ hipError_t launch_index_build(const IndexParams& p, hipStream_t st);
 hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st);
 hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+hipError_t launch_pack_weights(const void* B, void* out, int E, int K, int ldb, int n_tiles_n, int swiglu_F, hipStream_t st);
 hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalParams& a, int n_wg, hipStream_t st);
 hipError_t launch_tile_heights(const int32_t* kind, int32_t* height, int n, hipStream_t st);
 

@@ -37,7 +37,8 @@ class GpuLayer:
     """One plan + resident inputs; forward() can be called repeatedly."""
 
     def __init__(self, cfg: wl.MoEConfig, inp: wl.MoEInputs, ids: np.ndarray, w: np.ndarray,
-                 options: Optional[Dict[str, int]] = None):
+                 options: Optional[Dict[str, int]] = None, packed: bool = False):
+        """packed: the weights are re-laid out once with moe_pack_weights and the forwards take the packed buffers."""
         self.cfg = cfg
         self.plan = moe.moe_plan_create(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.act, inp.seg_offsets.tolist())
         for key, val in (options or {}).items():
@@ -45,6 +46,12 @@ class GpuLayer:
         self.x = dev_bf16(inp.x)
         self.W1 = dev_bf16(inp.W1) if inp.W1.size else torch.zeros(8, dtype=torch.bfloat16, device="cuda")
         self.W2 = dev_bf16(inp.W2) if inp.W2.size else torch.zeros(8, dtype=torch.bfloat16, device="cuda")
+        if packed and inp.W1.size:
+            W1p, W2p = torch.empty_like(self.W1), torch.empty_like(self.W2)
+            moe.moe_pack_weights(self.plan, self.W1, self.W2, W1p, W2p)
+            torch.cuda.synchronize()
+            self.W1, self.W2 = W1p, W2p          # the plain copies are dropped: a forward must not need them
+            moe.moe_plan_set_option(self.plan, "weights_packed", 1)
         self.ids = torch.from_numpy(ids).cuda()
         self.w = torch.from_numpy(w).cuda()
         self.out = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device="cuda")

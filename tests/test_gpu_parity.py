@@ -71,6 +71,26 @@ def test_layer_matches_oracle_small(H, cfg, tile_m):
         assert a <= H.REL_TOL and b <= H.REL_TOL
 
 
+@pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
+def test_packed_weights_give_the_same_bits(H, cfg):
+    """The plan-time weight re-layout changes where the operands come from, not what is summed in which order."""
+    print(f"packed case {cfg.name}", flush=True)
+    inp = wl.make_inputs(cfg, threads=4)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    ref = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act)
+    for tile_m in (64, 128, 256):
+        plain = H.GpuLayer(cfg, inp, ids, w, {"tile_m": tile_m})
+        plain.forward(); base = plain.results(); plain.close()
+        packed = H.GpuLayer(cfg, inp, ids, w, {"tile_m": tile_m}, packed=True)
+        packed.forward(); run = packed.results(); packed.close()
+        assert run.status == 0
+        a, b = H.error_metrics(run.out, ref)
+        print(f"  tile_m {tile_m}: err {a:.3e} {b:.3e}", flush=True)
+        assert a <= H.REL_TOL and b <= H.REL_TOL
+        np.testing.assert_array_equal(run.out, base.out)
+        np.testing.assert_array_equal(run.perm, base.perm)
+
+
 def test_router_matches_oracle(H):
     import paper_2502_19811_amd as moe
     for (T, E, k, seed) in [(128, 4, 2, 1), (513, 64, 8, 2), (100, 8, 8, 3), (77, 16, 1, 4), (64, 200, 6, 5)]:
