@@ -152,6 +152,17 @@ int moe_get_tile_table(const moe_plan_t *plan, const void *workspace, int32_t *n
                        void *hip_stream);
 int32_t moe_plan_max_tiles(const moe_plan_t *plan);
 
+/* The tile schedule of layer 0 or 1 as built by the last forward on this workspace (Fig. 5 / Fig. 6: the order in
+ * which GroupGEMM tiles are taken), for tests of its invariants.  items: dev int32 [moe_plan_schedule_capacity(plan,
+ * layer)][8] or NULL, records {m_tile, n_tile, expert, row0, nrows, height class 0/1/2, ready_seg, 0}; only the list
+ * positions named by the queues are meaningful.  queues: host int32 [24]: for XCD x the list position of its first
+ * item (queues[x]), its number of items (queues[8+x]) and the distance between consecutive items (queues[16+x]); a
+ * workgroup on XCD x takes its own queue front to back, then the others'.  Synchronises the stream.  The plan's
+ * schedule options must be the ones the forward ran with. */
+int moe_get_schedule(const moe_plan_t *plan, const void *workspace, int32_t layer, int32_t *items, int32_t *queues,
+                     void *hip_stream);
+int64_t moe_plan_schedule_capacity(const moe_plan_t *plan, int32_t layer);
+
 /* Stand-in for the peers on one GPU (for tests and the arrival experiment, Section 3.1.2 / Fig. 5): n_workgroups
  * workgroups (1..64) on the given stream copy the plan's source segments, in index order, from staging into the
  * receive buffer x (both dev bf16 [T,H]) at about gbytes_per_s in total (0 = unpaced), and after each segment

@@ -120,44 +120,14 @@ def segment_of_token(seg_offsets: np.ndarray, t: np.ndarray) -> np.ndarray:
     return (np.searchsorted(so, np.asarray(t, dtype=np.int64), side="right") - 1).astype(np.int32)
 
 
-def _tail_heights(rem: int, tile_m: int):
-    """Heights of the tiles that cover the last rem < tile_m rows of an expert with little padding."""
-    if rem == 0:
-        return []
-    if tile_m == 64 or rem <= 64:
-        return [64]
-    if rem <= 128 or tile_m == 128:
-        return [128]
-    if rem <= 192:
-        return [128, 64]
-    return [256]
+def rows_ready_segment(seg_offsets: np.ndarray, perm: np.ndarray, k: int, row0: int, nrows: int) -> int:
+    """Source segment a group of shared-tensor rows [row0, row0+nrows) has to wait for.
 
-
-def layer0_tiles(offsets: np.ndarray, perm: np.ndarray, k: int, seg_offsets: np.ndarray, tile_m: int):
-    """M-tiles of the layer0 GroupGEMM and the source segment each one waits for.
-
-    Every expert's row range is cut into tiles of ``tile_m`` rows; the remainder goes into shorter tiles
-    (64 / 128 rows, see ``_tail_heights``) so that little of a tile is padding.  A tile can start once all of
-    its rows have arrived (Section 2.2.1); with rows in source order that is when the segment of its LAST row
-    has arrived.  Returns int32 arrays expert, row0, nrows, ready_seg, height, in expert-major order."""
-    ex, r0, nr, rs, ht = [], [], [], [], []
-    E = len(offsets) - 1
-    for e in range(E):
-        lo, hi = int(offsets[e]), int(offsets[e + 1])
-        count = hi - lo
-        heights = [tile_m] * (count // tile_m) + _tail_heights(count % tile_m, tile_m)
-        a = lo
-        for h in heights:
-            b = min(hi, a + h)
-            ex.append(e)
-            r0.append(a)
-            nr.append(b - a)
-            ht.append(h)
-            rs.append(int(segment_of_token(seg_offsets, np.array([perm[b - 1] // k]))[0]))
-            a = b
-        assert a == hi
-    return (np.array(ex, np.int32), np.array(r0, np.int32), np.array(nr, np.int32), np.array(rs, np.int32),
-            np.array(ht, np.int32))
+    A GEMM tile cannot start before every token it needs has arrived (Section 2.2.1); segments arrive as wholes,
+    so the group is complete when the latest segment any of its rows comes from is there: the maximum over the
+    rows.  How rows are cut into tiles is a tuning choice of an implementation and no part of this oracle."""
+    toks = np.asarray(perm[row0:row0 + nrows], dtype=np.int64) // k
+    return int(segment_of_token(seg_offsets, toks).max())
 
 
 # --------------------------------------------------------------------------

@@ -12,7 +12,9 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     moe_get_index_outputs,
+    moe_get_schedule,
     moe_get_tile_table,
+    moe_plan_schedule_capacity,
     moe_last_device_status,
     moe_layer_forward,
     moe_pack_weights,

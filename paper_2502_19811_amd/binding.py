@@ -20,7 +20,8 @@ EXPORTS = [
     "moe_plan_workspace_bytes", "moe_plan_max_tiles", "moe_receive_buffer_bytes", "moe_route_topk",
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
     "moe_status_string", "moe_plan_phase_times", "moe_plan_forward_times", "moe_play_arrival",
-    "moe_probe_mfma", "moe_probe_copy", "moe_pack_weights",
+    "moe_probe_mfma", "moe_probe_copy", "moe_pack_weights", "moe_get_schedule",
+    "moe_plan_schedule_capacity",
 ]
 
 
@@ -71,6 +72,10 @@ def load_library():
     lib.moe_layer_forward.restype = C.c_int
     lib.moe_get_index_outputs.argtypes = [C.c_void_p, vp, i32p, i32p, i32p, i32p, vp]
     lib.moe_get_index_outputs.restype = C.c_int
+    lib.moe_get_schedule.argtypes = [C.c_void_p, vp, C.c_int32, i32p, C.POINTER(C.c_int32), vp]
+    lib.moe_get_schedule.restype = C.c_int
+    lib.moe_plan_schedule_capacity.argtypes = [C.c_void_p, C.c_int32]
+    lib.moe_plan_schedule_capacity.restype = C.c_int64
     lib.moe_get_tile_table.argtypes = [C.c_void_p, vp, i32p, i32p, i32p, i32p, i32p, i32p, vp]
     lib.moe_get_tile_table.restype = C.c_int
     lib.moe_last_device_status.argtypes = [C.c_void_p, vp, vp]
@@ -179,6 +184,19 @@ def moe_get_tile_table(plan: int, workspace, n_tiles, tile_expert, tile_row0, ti
                                              _ptr(tile_rows), _ptr(tile_ready_seg), _ptr(tile_height),
                                              _stream(stream)),
            "moe_get_tile_table")
+
+
+def moe_plan_schedule_capacity(plan: int, layer: int) -> int:
+    return load_library().moe_plan_schedule_capacity(plan, layer)
+
+
+def moe_get_schedule(plan: int, workspace, layer: int, items=None, stream=None):
+    """Queues of the last forward's tile schedule: (first position, items, stride) per XCD; items (a device int32
+    tensor [capacity, 8]) receives the item records."""
+    q = (C.c_int32 * 24)()
+    _check(load_library().moe_get_schedule(plan, _ptr(workspace), layer, _ptr(items), q, _stream(stream)),
+           "moe_get_schedule")
+    return [(q[x], q[8 + x], q[16 + x]) for x in range(8)]
 
 
 def moe_last_device_status(plan: int, workspace, stream=None) -> int:

@@ -486,6 +486,39 @@ int moe_get_tile_table(const moe_plan_t* p, const void* workspace, int32_t* n_ti
   return MOE_OK;
 }
 
+int64_t moe_plan_schedule_capacity(const moe_plan_t* p, int32_t layer) {
+  if (!p || (layer != 0 && layer != 1)) return 0;
+  return layer == 0 ? (int64_t)p->max_tiles * p->n_tiles_n0 : (int64_t)(p->max_tiles + 3 * kXcds) * p->n_tiles_n1;
+}
+
+int moe_get_schedule(const moe_plan_t* p, const void* workspace, int32_t layer, int32_t* items, int32_t* queues,
+                     void* hip_stream) {
+  if (!p || !workspace || !queues || (layer != 0 && layer != 1)) return MOE_ERR_INVALID_ARG;
+  Workspace ws = view(p, const_cast<void*>(workspace));
+  hipStream_t st = (hipStream_t)hip_stream;
+  int32_t status[64];
+  if (hipMemcpyAsync(status, ws.status, sizeof(status), hipMemcpyDeviceToHost, st) != hipSuccess) return MOE_ERR_HIP;
+  if (items) {
+    const size_t bytes = (size_t)moe_plan_schedule_capacity(p, layer) * sizeof(ItemRec);
+    if (bytes && hipMemcpyAsync(items, layer == 0 ? ws.items0 : ws.items1, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+      return MOE_ERR_HIP;
+  }
+  if (hipStreamSynchronize(st) != hipSuccess) return MOE_ERR_HIP;
+  const bool strided0 = !(p->layer0_order == 0 && !uses_large_schedule(p->max_tiles, p->large_schedule));
+  for (int x = 0; x < kXcds; x++) {
+    if (layer == 0) {
+      queues[x] = strided0 ? x : status[48 + x];
+      queues[kXcds + x] = status[24 + x];
+      queues[2 * kXcds + x] = strided0 ? kXcds : 1;
+    } else {
+      queues[x] = status[40 + x];
+      queues[kXcds + x] = status[32 + x];
+      queues[2 * kXcds + x] = 1;
+    }
+  }
+  return MOE_OK;
+}
+
 int moe_play_arrival(const moe_plan_t* p, const void* staging, void* x, uint32_t* seg_ready, uint32_t* seg_counters,
                      uint32_t ready_epoch, double gbytes_per_s, int32_t n_workgroups, void* hip_stream) {
   if (!p || !staging || !x || !seg_ready || !seg_counters) return MOE_ERR_INVALID_ARG;

@@ -82,6 +82,13 @@ class GpuLayer:
         return GpuRun(bf16_to_np(self.out), counts.cpu().numpy(), offsets.cpu().numpy(), perm[:cfg.R].cpu().numpy(),
                       inv[:cfg.R].cpu().numpy(), tiles, status)
 
+    def schedule(self, layer: int):
+        """(items [n, 8] int32 numpy, queues [(first, count, stride)] * 8) of the last forward's tile schedule."""
+        cap = max(moe.moe_plan_schedule_capacity(self.plan, layer), 1)
+        items = torch.zeros((cap, 8), dtype=torch.int32, device="cuda")
+        queues = moe.moe_get_schedule(self.plan, self.ws, layer, items)
+        return items.cpu().numpy(), queues
+
     def close(self):
         moe.moe_plan_destroy(self.plan)
         self.plan = None
@@ -94,3 +101,65 @@ def error_metrics(got: np.ndarray, ref: np.ndarray):
     a = float(diff.max() / max(np.abs(ref).max(), 1e-30)) if ref.size else 0.0
     b = float((diff / np.maximum(np.abs(ref), rms)).max()) if ref.size else 0.0
     return a, b
+
+
+def check_tile_table(tiles, cfg, offsets, perm, seg_offsets, tile_m):
+    """The M-tile table of a forward, checked through what any valid table has (the paper fixes no tile size or cut
+    rule: the rule is the library's): expert-major; the tiles of an expert partition its row range in order; heights
+    are kernel variants no taller than tile_m; a tile is full unless it is the expert's last; the segment it waits
+    for is the latest segment of its rows (Section 2.2.1), computed here from the oracle's row order."""
+    from oracle import moe_oracle as orc
+    ex, r0, nr, rs, ht = (np.asarray(tiles[key], dtype=np.int64) for key in ("expert", "row0", "rows", "ready_seg", "height"))
+    assert (np.diff(ex) >= 0).all(), "tile table is not expert-major"
+    assert np.isin(ht, (64, 128, 256)).all() and (ht <= tile_m).all()
+    assert (nr > 0).all() and (nr <= ht).all()
+    row_seg = orc.segment_of_token(seg_offsets, np.asarray(perm, dtype=np.int64) // cfg.k).astype(np.int64)
+    pos = 0
+    for e in range(cfg.E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        idx = np.nonzero(ex == e)[0]
+        if hi == lo:
+            assert idx.size == 0, f"expert {e} has no rows but {idx.size} tiles"
+            continue
+        assert idx.size > 0 and (np.diff(idx) == 1).all() and idx[0] == pos
+        pos += idx.size
+        assert r0[idx[0]] == lo and r0[idx[-1]] + nr[idx[-1]] == hi
+        assert (r0[idx[1:]] == r0[idx[:-1]] + nr[idx[:-1]]).all(), f"tiles of expert {e} leave a gap or overlap"
+        assert (nr[idx[:-1]] == ht[idx[:-1]]).all(), "only the last tile of an expert may be ragged"
+        # little padding: less than the smallest tile, unless the remainder needed a full-height ragged tile
+        pad = int(ht[idx].sum()) - (hi - lo)
+        assert 0 <= pad < 64 or ht[idx[-1]] == tile_m
+    assert pos == ex.size
+    for m in range(ex.size):
+        assert rs[m] == row_seg[r0[m]:r0[m] + nr[m]].max(), f"tile {m} waits for the wrong segment"
+
+
+def check_schedule(items, queues, tiles, n_tiles_n, order=None, seg_major=False, panel_major=False):
+    """Invariants of a tile schedule (Fig. 5 / Fig. 6): the queues list every (M-tile, column tile) pair exactly once,
+    every record repeats its M-tile's table row, tall tiles come before short ones inside a queue; seg_major: inside
+    a height class of a queue the segment waited for never decreases (rows that arrive early first); panel_major:
+    inside a height class of a queue the groups of 4 column panels ascend (all M-tiles finish a group before the
+    next one starts)."""
+    n_tiles = len(tiles["row0"])
+    seen = np.zeros((n_tiles, n_tiles_n), dtype=np.int32)
+    for first, count, stride in queues:
+        if count == 0:
+            continue
+        q = items[first:first + count * stride:stride]
+        assert len(q) == count
+        m, n = q[:, 0], q[:, 1]
+        assert (m >= 0).all() and (m < n_tiles).all() and (n >= 0).all() and (n < n_tiles_n).all()
+        np.add.at(seen, (m, n), 1)
+        np.testing.assert_array_equal(q[:, 2], tiles["expert"][m])
+        np.testing.assert_array_equal(q[:, 3], tiles["row0"][m])
+        np.testing.assert_array_equal(q[:, 4], tiles["rows"][m])
+        np.testing.assert_array_equal(64 << q[:, 5], tiles["height"][m])
+        np.testing.assert_array_equal(q[:, 6], tiles["ready_seg"][m])
+        assert (np.diff(q[:, 5]) <= 0).all(), "a taller tile after a shorter one"
+        for kind in (2, 1, 0):
+            part = q[q[:, 5] == kind]
+            if seg_major:
+                assert (np.diff(part[:, 6]) >= 0).all(), "segment order violated"
+            if panel_major:
+                assert (np.diff(part[:, 1] // 4) >= 0).all(), "column-panel groups out of order"
+    assert (seen == 1).all(), f"{int((seen == 0).sum())} items missing, {int((seen > 1).sum())} listed more than once"

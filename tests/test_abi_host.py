@@ -16,7 +16,7 @@ SEG8 = [0, 16, 32, 48, 64, 80, 96, 112, 128]
 def test_library_exports_every_declared_symbol():
     lib = moe.load_library()
     header = open(os.path.join(ROOT, "include", "moe_gfx950.h")).read()
-    declared = set(re.findall(r"^(?:int|size_t|int32_t|const char \*)\s*(moe_[a-z0-9_]+)\(", header, flags=re.M))
+    declared = set(re.findall(r"^(?:int|size_t|int32_t|int64_t|const char \*)\s*(moe_[a-z0-9_]+)\(", header, flags=re.M))
     assert declared, "no declarations found"
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared in the header but not exported"

@@ -38,6 +38,26 @@ def test_output_is_deterministic_and_independent_of_the_schedule():
         np.testing.assert_array_equal(r2.perm, base.perm)
 
 
+@pytest.mark.parametrize("opts", [{}, {"layer0_order": 1}, {"layer1_order": 1}, {"large_schedule": 1},
+                                  {"large_schedule": 1, "layer0_order": 1}, {"tile_m": 64, "block_m": 2},
+                                  ],
+                         ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()) or "default")
+def test_schedules_list_every_tile_once_in_the_documented_order(opts):
+    """The device-built schedules read back: once-only, records equal to the tile table, segment order for the
+    source-ordered layer0 list (Fig. 5) and panel-group order for the column-wise layer1 list (Fig. 6)."""
+    H, cfg, inp, ids, w, layer = _setup(dict(opts, phases=1))
+    layer.forward()
+    run = layer.results()
+    assert run.status == 0
+    n0 = cfg.F // (128 if cfg.act == wl.ACT_SWIGLU else 256)
+    n1 = cfg.H // 256
+    items0, q0 = layer.schedule(0)
+    items1, q1 = layer.schedule(1)
+    layer.close()
+    H.check_schedule(items0, q0, run.tiles, n0, seg_major=opts.get("layer0_order") == 1)
+    H.check_schedule(items1, q1, run.tiles, n1, panel_major=opts.get("layer1_order") == 1)
+
+
 def test_segment_boundaries_do_not_change_the_result():
     H, cfg, inp, ids, w, layer = _setup()
     layer.forward(); base = layer.results(); layer.close()
@@ -133,6 +153,33 @@ def test_paced_arrival_by_a_producer_workgroup():
     layer.close()
     assert run.status == 0
     assert flags.cpu().tolist() == [3] * cfg.S and counters.cpu().tolist() == [0] * cfg.S
+    np.testing.assert_array_equal(run.out, base.out)
+
+
+@pytest.mark.parametrize("order", [1, 0])
+def test_few_workgroups_walk_many_flagged_tiles(order):
+    """8 workgroups take the 48 layer0 items of the source-ordered schedule one after the other while a paced producer
+    raises the segment flags: a workgroup walks from a tile whose segment is there into successors whose segments
+    are not (no early start, blocking wait) and into ones that are (early start under flags).  Same bits as resident."""
+    import paper_2502_19811_amd as moe
+    H, cfg, inp, ids, w, layer = _setup({"n_cu": 8, "spin_limit": 1 << 26, "layer0_order": order})
+    layer.forward(); base = layer.results()
+    staging = layer.x.clone()
+    layer.x.zero_()
+    layer.out.zero_()
+    flags = torch.zeros(cfg.S, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(cfg.S, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    print(f"producer + 8-workgroup forward, layer0_order {order}", flush=True)
+    # 1 MB at 1 GB/s: a millisecond of arrivals against about 0.3 ms of layer0 work per workgroup
+    moe.moe_play_arrival(layer.plan, staging, layer.x, flags, counters, 9, 1.0, 2, side)
+    layer.forward(seg_ready=flags, epoch=9)
+    side.synchronize()
+    run = layer.results()
+    layer.close()
+    assert run.status == 0
+    assert flags.cpu().tolist() == [9] * cfg.S
     np.testing.assert_array_equal(run.out, base.out)
 
 

@@ -44,12 +44,8 @@ def _check_index(run, cfg, ids, seg_offsets, tile_m):
     np.testing.assert_array_equal(run.offsets, offsets)
     np.testing.assert_array_equal(run.perm, perm)
     np.testing.assert_array_equal(run.inv_perm, inv)
-    ex, r0, nr, rs, ht = orc.layer0_tiles(offsets, perm, cfg.k, seg_offsets, tile_m)
-    np.testing.assert_array_equal(run.tiles["expert"], ex)
-    np.testing.assert_array_equal(run.tiles["row0"], r0)
-    np.testing.assert_array_equal(run.tiles["rows"], nr)
-    np.testing.assert_array_equal(run.tiles["ready_seg"], rs)
-    np.testing.assert_array_equal(run.tiles["height"], ht)
+    import gpu_harness
+    gpu_harness.check_tile_table(run.tiles, cfg, offsets, perm, seg_offsets, tile_m)
 
 
 @pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)

@@ -115,29 +115,29 @@ def test_table3_buffer_sizes():
         assert orc.receive_buffer_bytes(M, N) == mb << 20
 
 
-# ---------------------------------------------------------------- tile readiness
-@pytest.mark.parametrize("tile_m", [64, 128, 256])
-def test_layer0_tiles_cover_rows_and_ready_segment(tile_m):
+# ---------------------------------------------------------------- readiness of groups of rows
+def test_rows_ready_segment_is_the_segment_of_the_last_row():
+    """Rows of an expert are in source order (Fig. 5), so the latest segment of any run of an expert's rows is the
+    segment of its last row; checked by brute force over every run of a few lengths."""
     cfg = wl.scaled(wl.CONFIGS["skewed"], T=700, E=8, k=2)
     seg = wl.segment_offsets(cfg)
     ids = _rand_ids(cfg.T, cfg.E, cfg.k, 9)
     _, offsets, perm, _ = orc.build_permutation(ids, cfg.E)
-    ex, r0, nr, rs, ht = orc.layer0_tiles(offsets, perm, cfg.k, seg, tile_m)
-    covered = np.zeros(cfg.R, np.int32)
-    for e, a, n, s, h in zip(ex, r0, nr, rs, ht):
-        assert 0 < n <= h <= tile_m and h in (64, 128, 256) and offsets[e] <= a and a + n <= offsets[e + 1]
-        assert n == h or a + n == offsets[e + 1]                          # only the last tile of an expert is ragged
-        covered[a:a + n] += 1
-        # brute force: the tile needs every row's source segment, i.e. the latest of them
-        toks = perm[a:a + n] // cfg.k
-        segs = [next(j for j in range(cfg.S) if seg[j] <= t < seg[j + 1]) for t in toks]
-        assert s == max(segs)
-        assert segs == sorted(segs)                                      # rows inside a tile are in source order
-    assert (covered == 1).all()
-    # padding: never more than 63 rows per expert unless the remainder needs the full-height tile
+
+    def seg_of(t):
+        return next(j for j in range(cfg.S) if seg[j] <= t < seg[j + 1])
+
     for e in range(cfg.E):
-        pad = int(ht[ex == e].sum()) - int(offsets[e + 1] - offsets[e])
-        assert 0 <= pad < 64
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        for n in (1, 7, 64):
+            for a in range(lo, max(lo, hi - n + 1), 13):
+                segs = [seg_of(int(perm[r]) // cfg.k) for r in range(a, a + n)]
+                assert segs == sorted(segs)
+                assert orc.rows_ready_segment(seg, perm, cfg.k, a, n) == max(segs) == segs[-1]
+    # across experts the order restarts: a run spanning two experts needs the maximum, not the last row
+    a = int(offsets[1]) - 3
+    segs = [seg_of(int(perm[r]) // cfg.k) for r in range(a, a + 6)]
+    assert orc.rows_ready_segment(seg, perm, cfg.k, a, 6) == max(segs)
 
 
 def test_segment_offsets_properties():
