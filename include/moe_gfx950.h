@@ -124,6 +124,20 @@ int moe_layer_forward(moe_plan_t *plan, const void *x, const int32_t *topk_ids, 
                       const void *W1, const void *W2, int32_t act, void *out, void *workspace,
                       size_t workspace_bytes, const uint32_t *seg_ready, uint32_t ready_epoch, void *hip_stream);
 
+/* moe_layer_forward for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same forward, same kernels and same results
+ * bit for bit, on a workspace that is a fixed 32 MiB array inside the library's device image (one copy per GPU, held
+ * until the process ends).  Allocates nothing and frees nothing.  A plan whose moe_plan_workspace_bytes exceeds
+ * 32 MiB (33554432 bytes) is refused with MOE_ERR_WORKSPACE_TOO_SMALL; use moe_layer_forward with a caller-owned
+ * workspace for such shapes.  All calls on one GPU share that GPU's array: a forward overwrites what the previous
+ * one left there (the index build of every forward resets the counters it needs), and two forwards that overlap in
+ * time on one GPU -- from different streams or threads -- race.  The array is not reachable through the getters that
+ * take a workspace pointer (index outputs, tile table, device status); callers that need those use moe_layer_forward.
+ * Other arguments, checks and return codes as for moe_layer_forward. */
+int moe_layer_forward_static(moe_plan_t *plan, const void *x, const int32_t *topk_ids, const float *topk_weights,
+                             const void *W1, const void *W2, int32_t act, void *out, const uint32_t *seg_ready,
+                             uint32_t ready_epoch, void *hip_stream);
+
 /* Plan-time re-layout of the expert weights for the GroupGEMM's operand path (Section 4: the GEMM operand pipeline;
  * Section 3.2.2: whatever is decided per shape is prepared before launch).  W1 [E,H,F1] and W2 [E,F,H] (dev bf16,
  * row-major as moe_layer_forward takes them) are rewritten into W1_packed / W2_packed (dev, same number of bytes

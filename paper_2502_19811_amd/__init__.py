@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     moe_plan_schedule_capacity,
     moe_last_device_status,
     moe_layer_forward,
+    moe_layer_forward_static,
     moe_pack_weights,
     moe_plan_create,
     moe_plan_destroy,

@@ -20,7 +20,7 @@ EXPORTS = [
     "moe_plan_workspace_bytes", "moe_plan_max_tiles", "moe_receive_buffer_bytes", "moe_route_topk",
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
     "moe_status_string", "moe_plan_phase_times", "moe_plan_forward_times", "moe_play_arrival",
-    "moe_probe_mfma", "moe_probe_copy", "moe_pack_weights", "moe_get_schedule",
+    "moe_probe_mfma", "moe_probe_copy", "moe_pack_weights", "moe_layer_forward_static", "moe_get_schedule",
     "moe_plan_schedule_capacity",
 ]
 
@@ -70,6 +70,8 @@ def load_library():
     lib.moe_layer_forward.argtypes = [C.c_void_p, vp, i32p, f32p, vp, vp, C.c_int32, vp, vp, C.c_size_t, u32p,
                                       C.c_uint32, vp]
     lib.moe_layer_forward.restype = C.c_int
+    lib.moe_layer_forward_static.argtypes = [C.c_void_p, vp, i32p, f32p, vp, vp, C.c_int32, vp, u32p, C.c_uint32, vp]
+    lib.moe_layer_forward_static.restype = C.c_int
     lib.moe_get_index_outputs.argtypes = [C.c_void_p, vp, i32p, i32p, i32p, i32p, vp]
     lib.moe_get_index_outputs.restype = C.c_int
     lib.moe_get_schedule.argtypes = [C.c_void_p, vp, C.c_int32, i32p, C.POINTER(C.c_int32), vp]
@@ -165,6 +167,14 @@ def moe_layer_forward(plan: int, x, topk_ids, topk_weights, W1, W2, act: int, ou
     _check(load_library().moe_layer_forward(plan, _ptr(x), _ptr(topk_ids), _ptr(topk_weights), _ptr(W1), _ptr(W2), act,
                                             _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _ptr(seg_ready), ready_epoch, _stream(stream)), "moe_layer_forward")
+
+
+def moe_layer_forward_static(plan: int, x, topk_ids, topk_weights, W1, W2, act: int, out, seg_ready=None,
+                             ready_epoch: int = 0, stream=None) -> None:
+    """moe_layer_forward on the library's own fixed workspace (no allocation; plans up to 32 MiB of workspace)."""
+    _check(load_library().moe_layer_forward_static(plan, _ptr(x), _ptr(topk_ids), _ptr(topk_weights), _ptr(W1), _ptr(W2),
+                                                   act, _ptr(out), _ptr(seg_ready), ready_epoch, _stream(stream)),
+           "moe_layer_forward_static")
 
 
 def moe_pack_weights(plan: int, W1, W2, W1_packed, W2_packed, stream=None) -> None:

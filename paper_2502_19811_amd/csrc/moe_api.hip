@@ -1,6 +1,7 @@
 // Host side of libmoe_gfx950: plan object, workspace layout, and the extern "C" entry points.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "moe_internal.h"
@@ -8,6 +9,13 @@
 using namespace moe;
 
 constexpr int kProfSlots = 64;
+
+// Workspace of moe_layer_forward_static: device memory that exists from the moment the library is loaded, so that a
+// forward on it allocates nothing.  Every GPU the library runs on holds its own copy at its own address; in host code
+// the array's name is only a handle for hipGetSymbolAddress, never a pointer to pass on.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 struct moe_plan {
   Shape s;
@@ -264,9 +272,13 @@ int moe_route_topk(const float* logits, int32_t T, int32_t E, int32_t k, int32_t
                                                                                                             : MOE_ERR_HIP;
 }
 
-int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, const float* topk_weights, const void* W1,
-                      const void* W2, int32_t act, void* out, void* workspace, size_t workspace_bytes,
-                      const uint32_t* seg_ready, uint32_t ready_epoch, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const float* topk_weights, const void* W1,
+                 const void* W2, int32_t act, void* out, void* workspace, size_t workspace_bytes,
+                 const uint32_t* seg_ready, uint32_t ready_epoch, void* hip_stream) {
   if (!p || !x || !topk_ids || !topk_weights || !W1 || !W2 || !out || !workspace) return MOE_ERR_INVALID_ARG;
   if (act != p->s.act) return MOE_ERR_SHAPE_MISMATCH;
   if (workspace_bytes < p->total_bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
@@ -408,6 +420,46 @@ int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, con
   if (!mark(4)) return MOE_ERR_HIP;
   if (ev) p->prof_steps++;
   return MOE_OK;
+}
+
+// Address of this device's copy of the static workspace, looked up once per device.
+int static_scratch(void** ptr) {
+  static std::mutex mu;
+  static void* per_device[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!per_device[dev]) {
+    void* a = nullptr;
+    if (hipGetSymbolAddress(&a, HIP_SYMBOL(scratch)) != hipSuccess || !a) return MOE_ERR_HIP;
+    per_device[dev] = a;
+  }
+  *ptr = per_device[dev];
+  return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_layer_forward(moe_plan_t* p, const void* x, const int32_t* topk_ids, const float* topk_weights, const void* W1,
+                      const void* W2, int32_t act, void* out, void* workspace, size_t workspace_bytes,
+                      const uint32_t* seg_ready, uint32_t ready_epoch, void* hip_stream) {
+  return forward_impl(p, x, topk_ids, topk_weights, W1, W2, act, out, workspace, workspace_bytes, seg_ready, ready_epoch,
+                      hip_stream);
+}
+
+int moe_layer_forward_static(moe_plan_t* p, const void* x, const int32_t* topk_ids, const float* topk_weights,
+                             const void* W1, const void* W2, int32_t act, void* out, const uint32_t* seg_ready,
+                             uint32_t ready_epoch, void* hip_stream) {
+  if (!p) return MOE_ERR_INVALID_ARG;
+  if (p->total_bytes > kStaticScratchBytes) return MOE_ERR_WORKSPACE_TOO_SMALL;   // the plan needs more than the fixed 32 MiB
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != MOE_OK) return rc;
+  return forward_impl(p, x, topk_ids, topk_weights, W1, W2, act, out, ws, kStaticScratchBytes, seg_ready, ready_epoch,
+                      hip_stream);
 }
 
 int moe_pack_weights(const moe_plan_t* p, const void* W1, const void* W2, void* W1_packed, void* W2_packed, void* hip_stream) {
