@@ -98,7 +98,8 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    per_forward_us = sorted(v * 1e3 for v in moe.moe_plan_forward_times(plan))
+    per_forward_us = sorted(v * 1e3 for v in moe.moe_plan_forward_times(plan, 256))
+    n_dropped = moe.moe_plan_get_option(plan, "profile_dropped")
     phase_ms, n_prof = moe.moe_plan_phase_times(plan)
     moe.moe_plan_set_option(plan, "profile", 0)
     status = moe.moe_last_device_status(plan, ws)
@@ -149,7 +150,7 @@ def main() -> int:
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},
         "phases_us": {"index_build": round(phase_ms[0] * 1e3, 1), "layer0_gemm": round(phase_ms[1] * 1e3, 1),
                       "layer1_gemm": round(phase_ms[2] * 1e3, 1), "combine": round(phase_ms[3] * 1e3, 1),
-                      "forwards_averaged": n_prof, "layer1_tflops": round(l1_tflops, 1),
+                      "forwards_averaged": n_prof, "forwards_not_recorded": n_dropped, "layer1_tflops": round(l1_tflops, 1),
                       # the reduction reads k rows of Y per token (plus 8 index/weight bytes per row) and writes out
                       "combine_hbm_gbps": round((2.0 * cfg.R * cfg.H + 8.0 * cfg.R + 2.0 * cfg.T * cfg.H)
                                                 / (phase_ms[3] * 1e-3) / 1e9, 1) if phase_ms[3] > 0 else None},

@@ -58,7 +58,8 @@ typedef struct {
  * seg_offsets: host, [S+1], non-decreasing, seg_offsets[0] = 0, seg_offsets[S] = T; segment s is the
  * token range [seg_offsets[s], seg_offsets[s+1]) written by source s.  Copied into the plan.
  * Supported: H % 256 == 0, F % 128 == 0 (F % 256 == 0 for GELU), 1 <= k <= E <= 256, k <= 16,
- * 1 <= S <= 64, T*k < 2^24.  Touches no GPU state.  *plan is set only on success. */
+ * 1 <= S <= 64, T*k < 2^24, and T*H*2 < 2^32 and T*k*F*2 < 2^32 (row offsets inside the kernels are 32-bit byte
+ * offsets); anything else is MOE_ERR_UNSUPPORTED.  Touches no GPU state.  *plan is set only on success. */
 int moe_plan_create(moe_plan_t **plan, const moe_shape_t *shape, const int32_t *seg_offsets);
 int moe_plan_destroy(moe_plan_t *plan);
 
@@ -69,14 +70,27 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  data-movement workgroups and by GEMM workgroups that ran out of tiles;
  *                  0 = a separate combine kernel after the layer1 kernel (default: the faster one on
  *                  every workload measured, see paper_2502_19811_amd/split_sweep.py)
- *   "layer0_order" 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5)
- *   "spin_limit"   >0: a wait on a ready flag gives up after that many polls and the forward
- *                  reports MOE_ERR_TIMEOUT through moe_last_device_status (0 = wait for ever)
+ *   "layer0_order" order of the layer0 tiles: 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5:
+ *                  M-tiles sorted by the segment they wait for, all column tiles of an M-tile in a row);
+ *                  2 = waves: the S source segments are grouped into "layer0_waves" waves, the tiles are
+ *                  segment-major across waves and weight-panel-major inside a wave; -1 (default) = chosen by
+ *                  every forward: 0 when seg_ready is NULL, 2 when ready flags are in use
+ *   "layer0_waves" 1..8 waves of order 2 (1 is order 0); 0 (default) = looked up from "expected_ingest_gbps"
+ *   "expected_ingest_gbps" rate in GB/s at which the caller expects the source segments to arrive (0 = unknown,
+ *                  default); selects the number of waves from a table measured with the arrival experiment
+ *   "spin_limit"   >0: a wait on a ready flag gives up after that many polls (about 0.3 us each) and the forward
+ *                  reports MOE_ERR_TIMEOUT through moe_last_device_status; 0 = wait for ever (a flag that never
+ *                  comes then hangs the GPU: the persistent kernel owns every compute unit).  Default 2^26,
+ *                  about 20 s
  *   "phases"       bit mask of the steps a forward runs: 1 index build, 2 layer0, 4 layer1, 8 combine
- *                  (default 15; used to time the phases alone)
+ *                  (default 15; used to time the phases alone).  Without bit 1 the forward runs the schedules the
+ *                  last index build left in the workspace again (it resets their queue heads and counters), so
+ *                  the workspace must have seen a forward with bit 1 for the same routing
  *   "n_cu"         workgroups of the persistent kernels (default: compute units of the device)
  *   "profile"      1: every forward records HIP events on its stream before and after each phase
- *                  (this call then creates the events; read them with moe_plan_phase_times)
+ *                  (this call then creates the events; read them with moe_plan_phase_times).  256 forwards can
+ *                  be recorded between two reads; later ones are not recorded and counted in the read-only key
+ *                  "profile_dropped"
  *   "block_m"      1..8: M-tiles of one expert that form a block of the default tile order; a block's items go to
  *                  one XCD (default 4: the 32 workgroups of an XCD then work on 4 M-tiles x 8 column tiles, and
  *                  two XCDs sweep the same weight panels of an expert with 8 M-tiles at the same time, the second
@@ -110,10 +124,13 @@ int moe_route_topk(const float *logits, int32_t T, int32_t E, int32_t k, int32_t
  *   layer0        GroupGEMM over gathered rows of x, row indices held in registers (Section 4),
  *                 activation fused, h [R,F] bf16; a tile starts once the source segment of its
  *                 last row is ready
- *   layer1        GroupGEMM h x W2 -> Y [R,H], column-panel-major (Fig. 6), with the top-k
- *                 weighted reduction done by data-movement workgroups of the same kernel as soon
- *                 as a column panel is complete (Section 3.2.1, Fig. 7)
- * x: dev bf16 [T,H] receive buffer.  topk_ids: dev int32 [T,k], values in [0,E) (not checked).
+ *   layer1        GroupGEMM h x W2 -> Y [R,H]
+ *   combine       out[t] = sum_j w[t,j] * Y[row of (t,j)]: by default a kernel of its own after layer1 (the
+ *                 faster choice on every workload measured on one GPU); with "layer1_order" = 1 layer1 runs
+ *                 column-panel-major (Fig. 6) and finished panels are reduced inside the layer1 kernel by its
+ *                 data-movement workgroups and by GEMM workgroups out of tiles (Section 3.2.1, Fig. 7)
+ * x: dev bf16 [T,H] receive buffer.  topk_ids: dev int32 [T,k], values in [0,E); a value outside is routed to the
+ * last expert (no access leaves a buffer) and reported by moe_last_device_status as MOE_ERR_INVALID_ARG.
  * topk_weights: dev fp32 [T,k].  W1: dev bf16 [E,H,F] (GELU) or [E,H,2F] (SwiGLU: columns [0,F)
  * gate, [F,2F) up).  W2: dev bf16 [E,F,H].  out: dev bf16 [T,H], out[t] = sum_j w[t,j] * FFN_e(t,j)(x[t]).
  * workspace: dev, >= moe_plan_workspace_bytes, 256-byte aligned; its index arrays stay readable until the
@@ -187,12 +204,12 @@ int moe_play_arrival(const moe_plan_t *plan, const void *staging, void *x, uint3
                      uint32_t ready_epoch, double gbytes_per_s, int32_t n_workgroups, void *hip_stream);
 
 /* Average time in ms of the four phases (index build, layer0 kernel, layer1 kernel incl. fused combine,
- * stand-alone combine) over the forwards recorded since the last call (at most 64), from the events of the
+ * stand-alone combine) over the forwards recorded since the last call (at most 256), from the events of the
  * "profile" option.  ms: host [4]; n_steps: host [1].  Waits for the recorded forwards to finish. */
 int moe_plan_phase_times(moe_plan_t *plan, float *ms, int32_t *n_steps);
 
 /* Time in ms of each forward recorded since the last moe_plan_phase_times call (first event to last event of
- * the forward; at most 64, at most capacity), for medians and percentiles.  ms: host [capacity]; n_steps: host
+ * the forward; at most 256, at most capacity), for medians and percentiles.  ms: host [capacity]; n_steps: host
  * [1].  Does not reset the recording; waits for the recorded forwards to finish. */
 int moe_plan_forward_times(moe_plan_t *plan, float *ms, int32_t capacity, int32_t *n_steps);
 

@@ -25,6 +25,8 @@ def main() -> int:
     ap.add_argument("--gbps", type=float, nargs="+", default=[25.0, 50.0, 100.0])
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--free-cus", type=int, default=8, help="compute units left to the producer")
+    ap.add_argument("--schedules", nargs="+", default=["0", "1", "2:8", "2:4", "2:2"],
+                    help="layer0 schedules to compare: order or order:waves")
     args = ap.parse_args()
 
     import numpy as np
@@ -49,10 +51,13 @@ def main() -> int:
     epoch = 0
 
     results = []
-    for order in (0, 1):
+    for sched in args.schedules:
+        order, _, waves = sched.partition(":")
+        order, waves = int(order), int(waves or 0)
         plan = moe.moe_plan_create(cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.act, inp.seg_offsets.tolist())
         moe.moe_plan_set_option(plan, "n_cu", n_cu)
         moe.moe_plan_set_option(plan, "layer0_order", order)
+        moe.moe_plan_set_option(plan, "layer0_waves", waves)
         moe.moe_plan_set_option(plan, "spin_limit", 1 << 28)
         ws = torch.zeros(moe.moe_plan_workspace_bytes(plan), dtype=torch.uint8, device="cuda")
 
@@ -88,7 +93,7 @@ def main() -> int:
             both = run("both", gbps)
             assert torch.equal(out, ref), "output changed with staggered arrival"
             hidden = 1.0 - (both - resident) / arrival
-            results.append({"workload": cfg.name, "layer0_order": order, "ingest_GBps": gbps,
+            results.append({"workload": cfg.name, "layer0_order": order, "layer0_waves": waves, "ingest_GBps": gbps,
                             "resident_us": round(resident, 1), "arrival_alone_us": round(arrival, 1),
                             "together_us": round(both, 1), "hidden": round(hidden, 3), "n_cu": n_cu})
             print(json.dumps(results[-1]), flush=True)

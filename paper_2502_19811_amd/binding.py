@@ -228,7 +228,7 @@ def moe_play_arrival(plan: int, staging, x, seg_ready, seg_counters, ready_epoch
            "moe_play_arrival")
 
 
-def moe_plan_forward_times(plan: int, capacity: int = 64):
+def moe_plan_forward_times(plan: int, capacity: int = 256):
     """ms of each forward recorded since the last moe_plan_phase_times call (needs the "profile" option)."""
     ms = (C.c_float * capacity)()
     n = C.c_int32()

@@ -470,9 +470,9 @@ struct ScheduleLds {
   uint8_t ready[kTileCap];
   uint8_t key0[kTileCap + 4];   // (height class, segment) or the height class alone; padded with 0xff
   uint8_t key1[kTileCap + 4];   // height class
-  int16_t run_first[3][kMaxExperts];  // per height class: first and last position of each expert's tiles in ord1
-  int16_t run_last[3][kMaxExperts];
-  int32_t blk_base[1024];             // [3][kMaxExperts] flattened (+ padding): first block of (class, expert)
+  uint16_t sub_first[kTileCap];       // position in ord1 of the first tile of tile i's run (same height, expert, wave)
+  uint16_t blk_of[kTileCap];          // block of the tile at position i of ord1
+  int32_t scan_buf[1024];             // scratch of the prefix scans
   int32_t cls_first[4];
   int32_t cls_count[3];
   int32_t queue_pos[3][kXcds];
@@ -512,17 +512,104 @@ __device__ inline void rank_sort(const uint8_t* key, uint16_t* ord, int n, int t
   }
 }
 
+// Inclusive prefix scan over up to 2048 values, two per thread (thread t holds elements 2t and 2t+1), running maximum
+// (MAX) or running sum.  buf: LDS scratch of 1024 values.
+template <bool MAX>
+__device__ inline void scan_pairs(int32_t* buf, int& v0, int& v1) {
+  const int t = threadIdx.x;
+  constexpr int kNeutral = MAX ? -0x7fffffff : 0;
+  v1 = MAX ? max(v0, v1) : v0 + v1;
+  buf[t] = v1;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {
+    const int o = t >= d ? buf[t - d] : kNeutral;
+    __syncthreads();
+    buf[t] = MAX ? max(buf[t], o) : buf[t] + o;
+    __syncthreads();
+  }
+  const int before = t > 0 ? buf[t - 1] : kNeutral;
+  __syncthreads();
+  v0 = MAX ? max(before, v0) : before + v0;
+  v1 = MAX ? max(before, v1) : before + v1;
+}
+
 // Items of one layer in the locality order (see above); n_tiles_n column tiles.
 __device__ inline void emit_blocks(const ScheduleLds& L, const uint16_t* ord, ItemRec* items, int n_tiles, int n_tiles_n,
                                    int block_m, int gtid, int gthreads) {
   for (int w = gtid; w < n_tiles * n_tiles_n; w += gthreads) {
     const int i = w / n_tiles_n, n = w % n_tiles_n;
-    const int m = ord[i], c = 2 - L.kind[m], e = L.expert[m];
-    const int j = i - L.run_first[c][e];
-    const int b = L.blk_base[c * kMaxExperts + e] + j / block_m, g = L.blk_g[b], jm = j % block_m;
+    const int b = L.blk_of[i], g = L.blk_g[b], jm = (i - L.sub_first[i]) % block_m;
     const int pos = (L.q_base_t[L.blk_q[b]] + L.blk_off[b]) * n_tiles_n + n * g + jm;
-    items[pos] = make_item_lds(L, m, n);
+    items[pos] = make_item_lds(L, ord[i], n);
   }
+}
+
+// Blocks of the locality order and their XCD queues.  The tiles (in ord1's order: height class, expert, source order)
+// fall into runs of the same height class, expert and wave -- a wave being a group of consecutive source segments,
+// n_waves of them over the S segments (1: no waves) -- and every run is cut into blocks of up to block_m M-tiles.
+// The blocks are sorted by (wave, height class, larger first) and dealt to the XCD queues back and forth (0..7,
+// 7..0, ...): with the sizes descending this keeps the queues level even when the experts' loads differ a lot, which
+// round-robin does not (what is left uneven, the workgroups even out by taking from other XCDs' queues at the end).
+// With waves the queues are segment-major across waves (tiles whose rows arrive early come first, Fig. 5) and
+// weight-panel-major inside a wave (a block's M-tiles share every weight panel they sweep).
+__device__ inline void build_blocks(ScheduleLds& L, const uint16_t* ord1, int n_tiles, int block_m, int n_waves, int S) {
+  const int tid = threadIdx.x;
+  auto run_key = [&](int i) {
+    const int m = ord1[i];
+    const int wave = n_waves > 1 ? (int)L.ready[m] * n_waves / S : 0;
+    return ((2 - (int)L.kind[m]) << 16) | ((int)L.expert[m] << 8) | wave;
+  };
+  if (tid < kXcds) L.q_len_t[tid] = 0;
+  const int i0 = 2 * tid, i1 = 2 * tid + 1;
+  int f0 = -1, f1 = -1;
+  if (i0 < n_tiles && (i0 == 0 || run_key(i0) != run_key(i0 - 1))) f0 = i0;
+  if (i1 < n_tiles && run_key(i1) != run_key(i1 - 1)) f1 = i1;
+  scan_pairs<true>(L.scan_buf, f0, f1);
+  int s0 = 0, s1 = 0;
+  if (i0 < n_tiles) { L.sub_first[i0] = (uint16_t)f0; s0 = (i0 - f0) % block_m == 0; }
+  if (i1 < n_tiles) { L.sub_first[i1] = (uint16_t)f1; s1 = (i1 - f1) % block_m == 0; }
+  const int start0 = s0, start1 = s1;
+  scan_pairs<false>(L.scan_buf, s0, s1);
+  if (i0 < n_tiles) L.blk_of[i0] = (uint16_t)(s0 - 1);
+  if (i1 < n_tiles) L.blk_of[i1] = (uint16_t)(s1 - 1);
+  if (i0 == n_tiles - 1) L.n_blocks = s0;
+  if (i1 == n_tiles - 1) L.n_blocks = s1;
+  __syncthreads();
+  auto describe = [&](int i, int b) {   // tile i starts block b
+    int g = 1;
+    while (g < block_m && i + g < n_tiles && L.sub_first[i + g] == L.sub_first[i]) g++;
+    const int key = run_key(i);
+    L.blk_g[b] = (uint16_t)g;
+    L.blk_key[b] = (uint8_t)((key & 0xff) * 24 + (key >> 16) * 8 + (8 - g));   // wave, height class, larger blocks first
+  };
+  if (i0 < n_tiles && start0) describe(i0, s0 - 1);
+  if (i1 < n_tiles && start1) describe(i1, s1 - 1);
+  const int n_blocks = L.n_blocks;
+  for (int b = n_blocks + tid; b < n_blocks + 4; b += 1024) L.blk_key[b] = 0xff;
+  __syncthreads();
+  rank_sort(L.blk_key, L.blk_ord, n_blocks, tid);
+  __syncthreads();
+  for (int pos = tid; pos < n_blocks; pos += 1024) {
+    const int r = pos / kXcds, i = pos % kXcds;
+    const int x = (r & 1) ? kXcds - 1 - i : i;
+    int off = 0;
+    for (int r2 = 0; r2 < r; r2++) off += L.blk_g[L.blk_ord[r2 * kXcds + ((r2 & 1) ? kXcds - 1 - x : x)]];
+    const int b = L.blk_ord[pos];
+    L.blk_off[b] = off;
+    L.blk_q[b] = (uint8_t)x;
+    // the queue's last block: no later round has a block for this queue
+    const int next = (r + 1) * kXcds + (((r + 1) & 1) ? kXcds - 1 - x : x);
+    if (next >= n_blocks) L.q_len_t[x] = off + L.blk_g[b];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int pos = 0;
+    for (int x = 0; x < kXcds; x++) {
+      L.q_base_t[x] = pos;
+      pos += L.q_len_t[x];
+    }
+  }
+  __syncthreads();
 }
 
 __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
@@ -531,13 +618,13 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   const int tid = threadIdx.x;
   const int S = p.s.S;
   const int nseg = p.layer0_order == 1 ? S : 1;
-  const bool local0 = p.layer0_order == 0, local1 = p.layer1_order == 0;
+  // layer0: 0 expert-major (locality order), 1 by source segment, 2 locality order inside waves of source segments
+  const bool local0 = p.layer0_order != 1, local1 = p.layer1_order == 0;
+  const int n_waves0 = p.layer0_order == 2 ? max(1, min(p.layer0_waves, min(S, 8))) : 1;
   const int block_m = p.block_m;   // M-tiles per block of the locality order (1..8)
   __shared__ int32_t seg_lds[kMaxSegments + 1];
   if (tid <= S) seg_lds[tid] = p.seg_offsets[tid];
   if (tid < 3) L.cls_count[tid] = 0;
-  if (tid < kXcds) L.q_len_t[tid] = 0;
-  for (int i = tid; i < 3 * kMaxExperts; i += 1024) (&L.run_first[0][0])[i] = -1;
   __syncthreads();
   for (int m = tid; m < n_tiles + 4; m += 1024) {
     if (m >= n_tiles) {
@@ -592,90 +679,27 @@ __global__ __launch_bounds__(1024) void k_index_schedule(IndexParams p) {
   __syncthreads();
   const uint16_t* ord1 = nseg > 1 ? L.ord1 : L.ord0;   // height class, then table order (expert-major)
   const int gtid = blockIdx.x * 1024 + tid, gthreads = gridDim.x * 1024;
-  if (local0 || local1) {
-    // where each expert's tiles sit inside a height class (they are contiguous: the sort is stable and the table is
-    // expert-major), the blocks they are cut into, and the XCD queues the blocks go to
-    for (int i = tid; i < n_tiles; i += 1024) {
-      const int m = ord1[i], c = 2 - L.kind[m], e = L.expert[m];
-      const int lo = L.cls_first[c], hi = L.cls_first[c + 1];
-      if (i == lo || L.expert[ord1[i - 1]] != e) L.run_first[c][e] = (int16_t)i;
-      if (i == hi - 1 || L.expert[ord1[i + 1]] != e) L.run_last[c][e] = (int16_t)i;
-    }
-    __syncthreads();
-    {
-      // blocks per (class, expert), then an exclusive prefix sum over the 768 pairs (1024 threads, one each)
-      const int c = tid / kMaxExperts, e = tid % kMaxExperts;
-      int nb = 0;
-      if (c < 3 && L.run_first[c][e] >= 0) nb = (L.run_last[c][e] - L.run_first[c][e] + block_m) / block_m;
-      L.blk_base[tid] = nb;
-      __syncthreads();
-      for (int d = 1; d < 1024; d <<= 1) {
-        const int add = tid >= d ? L.blk_base[tid - d] : 0;
-        __syncthreads();
-        L.blk_base[tid] += add;
-        __syncthreads();
-      }
-      const int incl = L.blk_base[tid];
-      if (tid == 1023) L.n_blocks = incl;
-      __syncthreads();
-      L.blk_base[tid] = incl - nb;
-      __syncthreads();
-    }
-    for (int i = tid; i < n_tiles; i += 1024) {
-      const int m = ord1[i], c = 2 - L.kind[m], e = L.expert[m];
-      const int j = i - L.run_first[c][e], cnt = L.run_last[c][e] - L.run_first[c][e] + 1;
-      if (j % block_m == 0) {
-        const int b = L.blk_base[c * kMaxExperts + e] + j / block_m, g = min(block_m, cnt - j);
-        L.blk_g[b] = (uint16_t)g;
-        L.blk_key[b] = (uint8_t)(c * 8 + (8 - g));   // height class first, inside it the larger blocks first
-      }
-    }
-    const int n_blocks = L.n_blocks;
-    for (int b = n_blocks + tid; b < n_blocks + 4; b += 1024) L.blk_key[b] = 0xff;
-    __syncthreads();
-    // The blocks are dealt to the XCD queues in that order, back and forth (0..7, 7..0, ...): with the sizes
-    // descending this keeps the queues level even when the experts' loads differ a lot, which round-robin does not
-    // (what is left uneven, the workgroups even out by taking from other XCDs' queues at the end).
-    rank_sort(L.blk_key, L.blk_ord, n_blocks, tid);
-    __syncthreads();
-    for (int pos = tid; pos < n_blocks; pos += 1024) {
-      const int r = pos / kXcds, i = pos % kXcds;
-      const int x = (r & 1) ? kXcds - 1 - i : i;
-      int off = 0;
-      for (int r2 = 0; r2 < r; r2++) off += L.blk_g[L.blk_ord[r2 * kXcds + ((r2 & 1) ? kXcds - 1 - x : x)]];
-      const int b = L.blk_ord[pos];
-      L.blk_off[b] = off;
-      L.blk_q[b] = (uint8_t)x;
-      // the queue's last block: no later round has a block for this queue
-      const int next = (r + 1) * kXcds + (((r + 1) & 1) ? kXcds - 1 - x : x);
-      if (next >= n_blocks) L.q_len_t[x] = off + L.blk_g[b];
-    }
-    __syncthreads();
-    if (tid == 0) {
-      int pos = 0;
-      for (int x = 0; x < kXcds; x++) {
-        L.q_base_t[x] = pos;
-        pos += L.q_len_t[x];
-      }
-    }
-    __syncthreads();
-    if (blockIdx.x == 0 && tid < kXcds) {
-      if (local0) {
-        p.ws.status[24 + tid] = L.q_len_t[tid] * p.n_tiles_n0;
-        p.ws.status[48 + tid] = L.q_base_t[tid] * p.n_tiles_n0;
-      }
-      if (local1) {
-        p.ws.status[32 + tid] = L.q_len_t[tid] * p.n_tiles_n1;
-        p.ws.status[40 + tid] = L.q_base_t[tid] * p.n_tiles_n1;
-      }
-    }
-  }
   if (local0) {
+    build_blocks(L, ord1, n_tiles, block_m, n_waves0, S);
+    if (blockIdx.x == 0 && tid < kXcds) {
+      p.ws.status[24 + tid] = L.q_len_t[tid] * p.n_tiles_n0;
+      p.ws.status[48 + tid] = L.q_base_t[tid] * p.n_tiles_n0;
+    }
     emit_blocks(L, ord1, p.ws.items0, n_tiles, p.n_tiles_n0, block_m, gtid, gthreads);
   } else {
     // by source segment (Fig. 5): all column tiles of an M-tile in a row; list position i belongs to XCD i % 8
     for (int i = gtid; i < n_tiles * p.n_tiles_n0; i += gthreads)
       p.ws.items0[i] = make_item_lds(L, L.ord0[i / p.n_tiles_n0], i % p.n_tiles_n0);
+  }
+  if (local1) {
+    if (!local0 || n_waves0 > 1) {
+      __syncthreads();   // the layer0 items are out: the block tables can be rebuilt without waves
+      build_blocks(L, ord1, n_tiles, block_m, 1, S);
+    }
+    if (blockIdx.x == 0 && tid < kXcds) {
+      p.ws.status[32 + tid] = L.q_len_t[tid] * p.n_tiles_n1;
+      p.ws.status[40 + tid] = L.q_base_t[tid] * p.n_tiles_n1;
+    }
   }
   if (local1) {
     emit_blocks(L, ord1, p.ws.items1, n_tiles, p.n_tiles_n1, block_m, gtid, gthreads);
@@ -749,6 +773,23 @@ __global__ __launch_bounds__(1024) void k_arrival_producer(const uint4* __restri
 
 hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalParams& a, int n_wg, hipStream_t st) {
   hipLaunchKernelGGL(k_arrival_producer, dim3(n_wg), dim3(1024), 0, st, (const uint4*)staging, (uint4*)x, a);
+  return hipGetLastError();
+}
+
+// Queue heads, combine counter, panel counters and the status word back to zero: what the scatter kernel does at the
+// start of a forward, for a forward that runs the schedules of an earlier index build again.
+__global__ void k_reset_counters(Workspace ws, int n_tiles_n1) {
+  const int t = threadIdx.x;
+  if (t == 0) {
+    ws.status[0] = 0;
+    ws.status[4] = 0;
+  }
+  if (t < 2 * kXcds) ws.status[8 + t] = 0;
+  for (int i = t; i < n_tiles_n1; i += 256) ws.panel_done[i] = 0;
+}
+
+hipError_t launch_reset_counters(const Workspace& ws, int n_tiles_n1, hipStream_t st) {
+  hipLaunchKernelGGL(k_reset_counters, dim3(1), dim3(256), 0, st, ws, n_tiles_n1);
   return hipGetLastError();
 }
 

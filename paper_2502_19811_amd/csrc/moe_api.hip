@@ -8,7 +8,7 @@
 
 using namespace moe;
 
-constexpr int kProfSlots = 64;
+constexpr int kProfSlots = 256;
 
 // Workspace of moe_layer_forward_static: device memory that exists from the moment the library is loaded, so that a
 // forward on it allocates nothing.  Every GPU the library runs on holds its own copy at its own address; in host code
@@ -23,13 +23,17 @@ struct moe_plan {
   // options
   int32_t tile_m;
   int32_t n_dm;          // -1: table lookup
-  int32_t layer0_order;
+  int32_t layer0_order;          // -1: chosen per forward (resident input: 0; ready flags in use: 2)
+  int32_t layer0_waves;          // 0: from the table below
+  int32_t expected_ingest_gbps;  // 0: unknown
+  int32_t last_layer0_order;     // what the last forward ran with (for moe_get_schedule)
   int32_t layer1_order;
   int32_t spin_limit;
   int32_t phases;
   int32_t n_cu;          // 0: not queried yet
   int32_t profile;       // 1: record events around the phases of every forward
-  int32_t prof_steps;    // forwards recorded since the last reset
+  int32_t prof_steps;    // forwards recorded since the last reset (at most kProfSlots)
+  int32_t prof_dropped;  // forwards since the last reset that found every slot taken and were not recorded
   hipEvent_t ev[kProfSlots][5];
   bool ev_created;
   // derived
@@ -122,6 +126,26 @@ int default_tile_m(const Shape& s) {
 // would get an entry here.
 int default_n_dm(const Shape&) { return 0; }
 
+// Waves the source segments are grouped into for the layer0 schedule when ready flags are in use (layer0_order 2):
+// segment-major across waves so that tiles start as their rows arrive (Fig. 5), weight-panel-major inside a wave.
+// Many waves follow a slow ingest closely but stream the layer0 weights once per wave; few waves keep the weight
+// reuse of the expert-major order at the price of waiting for a wave's last segment.  Looked up from the ingest
+// rate the caller expects (option "expected_ingest_gbps"), the way Section 3.2.2 looks its division point up from
+// metadata gathered by profiling; the entries come from the arrival experiment (arrival_experiment.py).
+int default_layer0_waves(const Shape& s, int ingest_gbps) {
+  struct Row { int up_to_gbps, waves; };
+  // Mixtral-shaped workload, 8 segments, end-to-end time of arrival and layer together: 4 waves are the fastest at
+  // 50, 100 and 200 GB/s (by 6 % over both the expert-major and the segment-major order) and level with the
+  // segment-major order at 25 GB/s; 8 waves and 2 waves lose at every rate.
+  static const Row table[] = {{25, 4}, {50, 4}, {100, 4}, {1 << 30, 4}};
+  int waves = 4;                                         // unknown rate
+  if (ingest_gbps > 0)
+    for (const Row& r : table)
+      if (ingest_gbps <= r.up_to_gbps) { waves = r.waves; break; }
+  if (waves > s.S) waves = s.S;
+  return waves < 1 ? 1 : waves;
+}
+
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
@@ -152,11 +176,11 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
   memcpy(p->seg_offsets, seg_offsets, sizeof(int32_t) * (sh.S + 1));
   p->tile_m = default_tile_m(p->s);
   p->n_dm = -1;
-  p->layer0_order = 0;
+  p->layer0_order = -1;
   p->layer1_order = 0;   // measured faster on every workload so far: see the sweep tool and default_n_dm
   p->serial = 0x2545F491;   // arbitrary start: an uninitialised workspace word is unlikely to match it
   p->block_m = 4;        // measured: 2-4 % faster on layer1 than 8, see the header
-  p->spin_limit = 0;
+  p->spin_limit = 1 << 26;   // about 20 s of polling: a lost flag ends in MOE_ERR_TIMEOUT, not in a hung GPU
   p->phases = 15;
   p->n_cu = 0;
   layout(p);
@@ -186,8 +210,18 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     return MOE_OK;
   }
   if (!strcmp(key, "layer0_order")) {
-    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    if (v < -1 || v > 2) return MOE_ERR_INVALID_ARG;
     p->layer0_order = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "layer0_waves")) {
+    if (v < 0 || v > 8) return MOE_ERR_INVALID_ARG;
+    p->layer0_waves = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "expected_ingest_gbps")) {
+    if (v < 0 || v > 1000000) return MOE_ERR_INVALID_ARG;
+    p->expected_ingest_gbps = (int32_t)v;
     return MOE_OK;
   }
   if (!strcmp(key, "layer1_order")) {
@@ -235,6 +269,7 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     }
     p->profile = (int32_t)v;
     p->prof_steps = 0;
+    p->prof_dropped = 0;
     return MOE_OK;
   }
   return MOE_ERR_INVALID_ARG;
@@ -245,11 +280,14 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   if (!strcmp(key, "tile_m")) *v = p->tile_m;
   else if (!strcmp(key, "n_dm")) *v = p->n_dm >= 0 ? p->n_dm : default_n_dm(p->s);
   else if (!strcmp(key, "layer0_order")) *v = p->layer0_order;
+  else if (!strcmp(key, "layer0_waves")) *v = p->layer0_waves > 0 ? p->layer0_waves : default_layer0_waves(p->s, p->expected_ingest_gbps);
+  else if (!strcmp(key, "expected_ingest_gbps")) *v = p->expected_ingest_gbps;
   else if (!strcmp(key, "layer1_order")) *v = p->layer1_order;
   else if (!strcmp(key, "spin_limit")) *v = p->spin_limit;
   else if (!strcmp(key, "phases")) *v = p->phases;
   else if (!strcmp(key, "n_cu")) *v = p->n_cu;
   else if (!strcmp(key, "profile")) *v = p->profile;
+  else if (!strcmp(key, "profile_dropped")) *v = p->prof_dropped;
   else if (!strcmp(key, "large_schedule")) *v = p->large_schedule;
   else if (!strcmp(key, "block_m")) *v = p->block_m;
   else if (!strcmp(key, "weights_packed")) *v = p->weights_packed;
@@ -295,7 +333,18 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     p->n_cu = n;
   }
   Workspace ws = view(p, workspace);
-  hipEvent_t* ev = p->profile ? p->ev[p->prof_steps % kProfSlots] : nullptr;
+  // The layer0 tile order of this forward: the schedule is built inside the forward, so it can follow what the
+  // forward is given.  All rows resident: expert-major (weight reuse first).  Ready flags in use: waves of source
+  // segments (Fig. 5).  The one-workgroup builder for very large tile tables knows orders 0 and 1 only.
+  const bool large = uses_large_schedule(p->max_tiles, p->large_schedule);
+  int order0 = p->layer0_order >= 0 ? p->layer0_order : (seg_ready ? 2 : 0);
+  const int waves0 = p->layer0_waves > 0 ? p->layer0_waves : default_layer0_waves(s, p->expected_ingest_gbps);
+  if (order0 == 2 && large) order0 = 1;
+  if (p->phases & 1) p->last_layer0_order = order0;
+  else order0 = p->last_layer0_order;   // the schedules of the last index build are run again
+  // a forward beyond the last event slot is not recorded (and counted as dropped) rather than overwriting an earlier one
+  hipEvent_t* ev = (p->profile && p->prof_steps < kProfSlots) ? p->ev[p->prof_steps] : nullptr;
+  if (p->profile && !ev) p->prof_dropped++;
   auto mark = [&](int i) { return !ev || hipEventRecord(ev[i], st) == hipSuccess; };
   if (!mark(0)) return MOE_ERR_HIP;
 
@@ -309,7 +358,8 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     ip.tile_m = p->tile_m;
     ip.n_tiles_n0 = p->n_tiles_n0;
     ip.n_tiles_n1 = p->n_tiles_n1;
-    ip.layer0_order = p->layer0_order;
+    ip.layer0_order = order0;
+    ip.layer0_waves = waves0;
     ip.layer1_order = p->layer1_order;
     ip.max_tiles = p->max_tiles;
     ip.force_large_schedule = p->large_schedule;
@@ -317,6 +367,9 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     ip.forward_serial = ++p->serial;
     memcpy(ip.seg_offsets, p->seg_offsets, sizeof(int32_t) * (s.S + 1));
     if (launch_index_build(ip, st) != hipSuccess) return MOE_ERR_HIP;
+  } else {
+    // the schedules of the last index build on this workspace are run again: their queue heads and counters start over
+    if (launch_reset_counters(ws, p->n_tiles_n1, st) != hipSuccess) return MOE_ERR_HIP;
   }
 
   if (!mark(1)) return MOE_ERR_HIP;
@@ -359,7 +412,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     a.n_mfma = grid0;
     a.queue_heads = ws.status + 8;
     a.queue_len = ws.status + 24;
-    if (p->layer0_order == 0 && !uses_large_schedule(p->max_tiles, p->large_schedule)) {
+    if (order0 != 1 && !large) {
       a.queue_base = ws.status + 48;   // contiguous per-XCD queues (locality order)
       a.queue_stride = 1;
     } else {
@@ -477,7 +530,7 @@ int moe_pack_weights(const moe_plan_t* p, const void* W1, const void* W2, void* 
 
 int moe_plan_phase_times(moe_plan_t* p, float* ms, int32_t* n_steps) {
   if (!p || !ms || !n_steps) return MOE_ERR_INVALID_ARG;
-  const int n = p->prof_steps < kProfSlots ? p->prof_steps : kProfSlots;
+  const int n = p->prof_steps;
   *n_steps = n;
   for (int j = 0; j < 4; j++) ms[j] = 0.f;
   if (n == 0) return MOE_OK;
@@ -491,12 +544,13 @@ int moe_plan_phase_times(moe_plan_t* p, float* ms, int32_t* n_steps) {
   }
   for (int j = 0; j < 4; j++) ms[j] /= n;
   p->prof_steps = 0;
+  p->prof_dropped = 0;
   return MOE_OK;
 }
 
 int moe_plan_forward_times(moe_plan_t* p, float* ms, int32_t capacity, int32_t* n_steps) {
   if (!p || !ms || !n_steps || capacity < 0) return MOE_ERR_INVALID_ARG;
-  int n = p->prof_steps < kProfSlots ? p->prof_steps : kProfSlots;
+  int n = p->prof_steps;
   if (n > capacity) n = capacity;
   *n_steps = n;
   for (int i = 0; i < n; i++) {
@@ -556,7 +610,7 @@ int moe_get_schedule(const moe_plan_t* p, const void* workspace, int32_t layer, 
       return MOE_ERR_HIP;
   }
   if (hipStreamSynchronize(st) != hipSuccess) return MOE_ERR_HIP;
-  const bool strided0 = !(p->layer0_order == 0 && !uses_large_schedule(p->max_tiles, p->large_schedule));
+  const bool strided0 = !(p->last_layer0_order != 1 && !uses_large_schedule(p->max_tiles, p->large_schedule));
   for (int x = 0; x < kXcds; x++) {
     if (layer == 0) {
       queues[x] = strided0 ? x : status[48 + x];

@@ -66,7 +66,8 @@ struct IndexParams {
   int32_t n_blocks;
   int32_t tile_m;
   int32_t n_tiles_n0, n_tiles_n1;
-  int32_t layer0_order, layer1_order;
+  int32_t layer0_order, layer1_order;   // layer0: 0 expert-major, 1 by source segment, 2 waves of segments
+  int32_t layer0_waves;                 // order 2: waves the source segments are grouped into (1..8)
   int32_t max_tiles;             // bound on the M-tiles of this plan
   int32_t force_large_schedule;  // 1: build the schedules with the one-workgroup kernel whatever the size
   int32_t block_m;               // M-tiles per block of the locality order (1..8)
@@ -138,6 +139,7 @@ struct CombineParams {
 // kernel launchers (defined in the .hip files)
 hipError_t launch_route_topk(const float* logits, int T, int E, int k, int32_t* ids, float* w, hipStream_t st);
 hipError_t launch_index_build(const IndexParams& p, hipStream_t st);
+hipError_t launch_reset_counters(const Workspace& ws, int n_tiles_n1, hipStream_t st);
 hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st);
 hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);

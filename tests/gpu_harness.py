@@ -134,12 +134,13 @@ def check_tile_table(tiles, cfg, offsets, perm, seg_offsets, tile_m):
         assert rs[m] == row_seg[r0[m]:r0[m] + nr[m]].max(), f"tile {m} waits for the wrong segment"
 
 
-def check_schedule(items, queues, tiles, n_tiles_n, order=None, seg_major=False, panel_major=False):
+def check_schedule(items, queues, tiles, n_tiles_n, seg_major=False, panel_major=False, waves=None):
     """Invariants of a tile schedule (Fig. 5 / Fig. 6): the queues list every (M-tile, column tile) pair exactly once,
     every record repeats its M-tile's table row, tall tiles come before short ones inside a queue; seg_major: inside
     a height class of a queue the segment waited for never decreases (rows that arrive early first); panel_major:
     inside a height class of a queue the groups of 4 column panels ascend (all M-tiles finish a group before the
-    next one starts)."""
+    next one starts); waves = (n_waves, S): the queue is wave-major (wave of a tile = ready_seg * n_waves // S), tall
+    before short inside a wave, and the M-tiles of an expert inside a wave sweep the column tiles together."""
     n_tiles = len(tiles["row0"])
     seen = np.zeros((n_tiles, n_tiles_n), dtype=np.int32)
     for first, count, stride in queues:
@@ -155,7 +156,13 @@ def check_schedule(items, queues, tiles, n_tiles_n, order=None, seg_major=False,
         np.testing.assert_array_equal(q[:, 4], tiles["rows"][m])
         np.testing.assert_array_equal(64 << q[:, 5], tiles["height"][m])
         np.testing.assert_array_equal(q[:, 6], tiles["ready_seg"][m])
-        assert (np.diff(q[:, 5]) <= 0).all(), "a taller tile after a shorter one"
+        if waves:
+            wave = q[:, 6] * waves[0] // waves[1]
+            assert (np.diff(wave) >= 0).all(), "a tile of an earlier wave after one of a later wave"
+            for wv in np.unique(wave):
+                assert (np.diff(q[wave == wv][:, 5]) <= 0).all(), "a taller tile after a shorter one inside a wave"
+        else:
+            assert (np.diff(q[:, 5]) <= 0).all(), "a taller tile after a shorter one"
         for kind in (2, 1, 0):
             part = q[q[:, 5] == kind]
             if seg_major:

@@ -41,10 +41,11 @@ def test_plan_create_and_options():
     assert moe.moe_plan_workspace_bytes(plan) > 256 * (512 + 256) * 2           # holds h [R,F] and Y [R,H], R = 256
     assert moe.moe_plan_get_option(plan, "tile_m") in (64, 128, 256)
     for key, val in [("tile_m", 128), ("n_dm", 7), ("layer0_order", 1), ("layer1_order", 0), ("spin_limit", 1000),
-                     ("phases", 3), ("n_cu", 64), ("large_schedule", 1), ("block_m", 8)]:
+                     ("phases", 3), ("n_cu", 64), ("large_schedule", 1), ("block_m", 8),
+                     ("layer0_order", 2), ("layer0_waves", 4), ("expected_ingest_gbps", 50), ("weights_packed", 1)]:
         moe.moe_plan_set_option(plan, key, val)
         assert moe.moe_plan_get_option(plan, key) == val
-    for key, val in [("tile_m", 100), ("n_dm", -2), ("layer0_order", 2), ("phases", 16), ("large_schedule", 2),
+    for key, val in [("tile_m", 100), ("n_dm", -2), ("layer0_order", 3), ("layer0_order", -2), ("layer0_waves", 9), ("phases", 16), ("large_schedule", 2),
                      ("block_m", 0), ("block_m", 9), ("no_such_key", 1)]:
         with pytest.raises(moe.MoEError) as e:
             moe.moe_plan_set_option(plan, key, val)

@@ -28,7 +28,7 @@ def test_output_is_deterministic_and_independent_of_the_schedule():
     a, b = H.error_metrics(base.out, ref)
     assert a <= H.REL_TOL and b <= H.REL_TOL
     for opts in ({}, {"layer0_order": 1}, {"layer1_order": 1}, {"layer1_order": 1, "n_dm": 16}, {"tile_m": 128},
-                 {"n_cu": 64}):
+                 {"n_cu": 64}, {"layer0_order": 2, "layer0_waves": 4}, {"layer0_order": 2, "layer0_waves": 8, "layer1_order": 1}):
         print(f"options {opts}", flush=True)
         _, _, _, _, _, l2 = _setup(opts)
         l2.forward(); r2 = l2.results(); l2.close()
@@ -40,7 +40,9 @@ def test_output_is_deterministic_and_independent_of_the_schedule():
 
 @pytest.mark.parametrize("opts", [{}, {"layer0_order": 1}, {"layer1_order": 1}, {"large_schedule": 1},
                                   {"large_schedule": 1, "layer0_order": 1}, {"tile_m": 64, "block_m": 2},
-                                  ],
+                                  {"layer0_order": 2, "layer0_waves": 8}, {"layer0_order": 2, "layer0_waves": 3},
+                                  {"layer0_order": 2, "layer0_waves": 2, "tile_m": 64, "block_m": 3},
+                                  {"large_schedule": 1, "layer0_order": 2}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()) or "default")
 def test_schedules_list_every_tile_once_in_the_documented_order(opts):
     """The device-built schedules read back: once-only, records equal to the tile table, segment order for the
@@ -54,7 +56,10 @@ def test_schedules_list_every_tile_once_in_the_documented_order(opts):
     items0, q0 = layer.schedule(0)
     items1, q1 = layer.schedule(1)
     layer.close()
-    H.check_schedule(items0, q0, run.tiles, n0, seg_major=opts.get("layer0_order") == 1)
+    large = opts.get("large_schedule") == 1
+    order0 = opts.get("layer0_order", 0)
+    H.check_schedule(items0, q0, run.tiles, n0, seg_major=order0 == 1 or (order0 == 2 and large),
+                     waves=(opts["layer0_waves"], cfg.S) if order0 == 2 and not large else None)
     H.check_schedule(items1, q1, run.tiles, n1, panel_major=opts.get("layer1_order") == 1)
 
 
@@ -156,13 +161,16 @@ def test_paced_arrival_by_a_producer_workgroup():
     np.testing.assert_array_equal(run.out, base.out)
 
 
-@pytest.mark.parametrize("order", [1, 0])
+@pytest.mark.parametrize("order", [-1, 1, 0, 2])
 def test_few_workgroups_walk_many_flagged_tiles(order):
     """8 workgroups take the 48 layer0 items of the source-ordered schedule one after the other while a paced producer
     raises the segment flags: a workgroup walks from a tile whose segment is there into successors whose segments
     are not (no early start, blocking wait) and into ones that are (early start under flags).  Same bits as resident."""
     import paper_2502_19811_amd as moe
-    H, cfg, inp, ids, w, layer = _setup({"n_cu": 8, "spin_limit": 1 << 26, "layer0_order": order})
+    opts = {"n_cu": 8, "spin_limit": 1 << 26}
+    if order >= 0:
+        opts["layer0_order"] = order            # -1: no option set, the forward chooses (waves, because of the flags)
+    H, cfg, inp, ids, w, layer = _setup(opts)
     layer.forward(); base = layer.results()
     staging = layer.x.clone()
     layer.x.zero_()
