@@ -29,8 +29,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mixtral", help="tiny | mixtral | qwen2 | phi35 | skewed")
     ap.add_argument("--opt", action="append", default=[], help="plan option key=value (repeatable)")
-    ap.add_argument("--packed", type=int, default=0, choices=[0, 1],
-                    help="1: the weights are re-laid out once, before the timed steps, with moe_pack_weights")
+    ap.add_argument("--packed", type=int, default=1, choices=[0, 1],
+                    help="1 (default): the weights are re-laid out once, before the timed steps, with moe_pack_weights; "
+                         "the layer is then also timed on the plain weights (10 steps, reported as plain_weights)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
                     help="tokens the CPU oracle is timed (and the GPU output checked) on; 8192 is the whole default workload")
@@ -69,9 +70,10 @@ def main() -> int:
     for kv in args.opt:
         key, val = kv.split("=")
         moe.moe_plan_set_option(plan, key, int(val))
+    W1_plain, W2_plain = W1, W2
     if args.packed:
         W1p, W2p = torch.empty_like(W1), torch.empty_like(W2)
-        moe.moe_pack_weights(plan, W1, W2, W1p, W2p)
+        moe.moe_pack_weights(plan, W1, W2, W1p, W2p)      # plan-time, outside the timed region
         torch.cuda.synchronize()
         W1, W2 = W1p, W2p
         del W1p, W2p
@@ -112,14 +114,34 @@ def main() -> int:
     l1_flop = 2.0 * cfg.R * cfg.F * cfg.H
     l0_tflops = l0_flop / (phase_ms[1] * 1e-3) / 1e12 if phase_ms[1] > 0 else 0.0
     l1_tflops = l1_flop / (phase_ms[2] * 1e-3) / 1e12 if phase_ms[2] > 0 else 0.0
-    # HBM-side bytes per launch of that kernel, from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
-    # each scaled by what the counter reads for a plain 1 GiB copy); None if no summary exists for this workload
+    # Bytes per launch of that kernel between the L2s and the memory side, from the committed rocprofv3 --pmc summary
+    # (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB copy); None if no summary
+    # exists for this workload.  The counters sit at the L2s: reads served by the Infinity Cache are included, and
+    # rocprofv3 offers no counter behind it on this device, so the HBM share cannot be separated.
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"group_gemm_{cfg.name}_pmc_traffic.md")
     if os.path.exists(tpath):
         for line in open(tpath):
-            if line.startswith("hbm_bytes_per_launch layer0:"):
+            if line.startswith("l2_fabric_bytes_per_launch layer0:"):
                 traffic = float(line.split(":")[1])
+
+    # the same layer on the plain row-major weights, for comparison (not the headline: 10 steps)
+    plain = None
+    if args.packed:
+        moe.moe_plan_set_option(plan, "weights_packed", 0)
+        for _ in range(3):
+            moe.moe_layer_forward(plan, x, ids, w, W1_plain, W2_plain, cfg.act, out, ws, None, 0, stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(10):
+            moe.moe_layer_forward(plan, x, ids, w, W1_plain, W2_plain, cfg.act, out, ws, None, 0, stream)
+        torch.cuda.synchronize()
+        ms_plain = (time.perf_counter() - t1) / 10 * 1e3
+        plain = {"us_per_layer": round(ms_plain * 1e3, 1), "tflops": round(cfg.flops / (ms_plain * 1e-3) / 1e12, 2),
+                 "frac_of_bf16_peak": round(cfg.flops / (ms_plain * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "steps": 10}
+        moe.moe_plan_set_option(plan, "weights_packed", 1)
+        step()                              # the output checked below comes from the packed path
+        torch.cuda.synchronize()
 
     result = {
         "metric": METRIC,
@@ -156,7 +178,10 @@ def main() -> int:
                                                 / (phase_ms[3] * 1e-3) / 1e9, 1) if phase_ms[3] > 0 else None},
         "roofline": {"bound": "mfma", "kernel": "k_group_gemm layer0 (fc1 + activation)", "achieved": round(l0_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(l0_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": traffic},
+                     "traffic": traffic,
+                     "traffic_is": "bytes between the L2s and the memory side (FETCH_SIZE + WRITE_SIZE), Infinity Cache "
+                                   "hits included; no HBM-level counter is available"},
+        "plain_weights": plain,
     }
 
     # what this board sustains with the same MFMA instruction from registers, and its copy rate: context for the

@@ -214,14 +214,22 @@ int moe_plan_phase_times(moe_plan_t *plan, float *ms, int32_t *n_steps);
 int moe_plan_forward_times(moe_plan_t *plan, float *ms, int32_t capacity, int32_t *n_steps);
 
 /* Measurement aids (no part of the paper's method): ceilings of the device, measured by the library's own probe
- * kernels, to read the layer's figures against.  Both create and destroy two events, enqueue on the given stream
+ * kernels, to read the layer's figures against.  All create and destroy two events, enqueue on the given stream
  * and wait for their own work to finish.
  * moe_probe_mfma: a register-only loop of v_mfma_f32_32x32x16_bf16, 16 accumulator blocks per wavefront, one
  *   workgroup of 4 wavefronts per compute unit, iters x 16 instructions per wavefront; random_data != 0: random bf16
  *   operands, else zeros (zeros draw less power and clock higher).  scratch: dev, at least compute units x 1 KiB
  *   (overwritten).  tflops: host [1].
  * moe_probe_copy: plain device copy of bytes (multiple of 16, both pointers 16-byte aligned) from src to dst;
- *   gbytes_per_s: host [1], bytes read plus bytes written per second. */
+ *   gbytes_per_s: host [1], bytes read plus bytes written per second.
+ * moe_probe_mix: the same MFMA loop on random data with the data movement of a GroupGEMM K step around it, to price
+ *   each kind of traffic at the board's power limit: mode is a bit mask -- 1: 8 ds_read_b128 per 16 MFMAs refresh the
+ *   operand fragments from LDS; 2: 4 global->LDS loads of 1 KiB per 16 MFMAs from an L2-resident region; 4: a
+ *   workgroup barrier per 16 MFMAs; 8 (needs 2): one load in four streams from HBM instead.  The loop runs twice
+ *   (warm-up, then timed), iters x 16 MFMAs per wavefront each.  scratch: dev, 16-byte aligned, at least 4 MiB, with
+ *   bit 8 at least 4 MiB x (compute units + 1); its contents are read as operands and partly overwritten.
+ *   tflops: host [1]. */
+int moe_probe_mix(int32_t mode, int32_t iters, void *scratch, size_t scratch_bytes, float *tflops, void *hip_stream);
 int moe_probe_mfma(int32_t random_data, int32_t iters, void *scratch, size_t scratch_bytes, float *tflops,
                    void *hip_stream);
 int moe_probe_copy(void *dst, const void *src, size_t bytes, float *gbytes_per_s, void *hip_stream);

@@ -30,6 +30,7 @@ from .binding import (  # noqa: F401
     moe_play_arrival,
     moe_probe_copy,
     moe_probe_mfma,
+    moe_probe_mix,
     moe_receive_buffer_bytes,
     moe_route_topk,
     moe_status_string,

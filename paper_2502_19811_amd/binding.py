@@ -21,7 +21,7 @@ EXPORTS = [
     "moe_layer_forward", "moe_get_index_outputs", "moe_get_tile_table", "moe_last_device_status",
     "moe_status_string", "moe_plan_phase_times", "moe_plan_forward_times", "moe_play_arrival",
     "moe_probe_mfma", "moe_probe_copy", "moe_pack_weights", "moe_layer_forward_static", "moe_get_schedule",
-    "moe_plan_schedule_capacity",
+    "moe_plan_schedule_capacity", "moe_probe_mix",
 ]
 
 
@@ -88,6 +88,8 @@ def load_library():
     lib.moe_plan_forward_times.restype = C.c_int
     lib.moe_probe_mfma.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, C.POINTER(C.c_float), vp]
     lib.moe_probe_mfma.restype = C.c_int
+    lib.moe_probe_mix.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, C.POINTER(C.c_float), vp]
+    lib.moe_probe_mix.restype = C.c_int
     lib.moe_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_float), vp]
     lib.moe_probe_copy.restype = C.c_int
     lib.moe_play_arrival.argtypes = [C.c_void_p, vp, vp, u32p, u32p, C.c_uint32, C.c_double, C.c_int32, vp]
@@ -241,6 +243,15 @@ def moe_probe_mfma(random_data: bool, iters: int, scratch, stream=None) -> float
     out = C.c_float()
     _check(load_library().moe_probe_mfma(int(bool(random_data)), iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
                                          C.byref(out), _stream(stream)), "moe_probe_mfma")
+    return float(out.value)
+
+
+def moe_probe_mix(mode: int, iters: int, scratch, stream=None) -> float:
+    """TFLOP/s of the MFMA loop with GroupGEMM-like data movement around it (mode bits: 1 LDS reads, 2 global->LDS
+    loads, 4 barrier, 8 a quarter of the loads from HBM); scratch: a device tensor, see the header for its size."""
+    out = C.c_float()
+    _check(load_library().moe_probe_mix(mode, iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                        C.byref(out), _stream(stream)), "moe_probe_mix")
     return float(out.value)
 
 

@@ -491,6 +491,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       }
     }
   }
+#ifdef MOE_EXP_ACQ
+  if (MODE == MODE_L1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
   // address set-up and the first loads (A blocks 0..2, B stages 0..2)
   LoadState ls;
   setup_and_issue<WM, MT, NT, MODE, PK>(p, lds0, cur, ls, lane, w, !cur.pre);
@@ -671,6 +674,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     publish_panel(p, pending_panel);
     pending_panel = -1;
   }
+#ifdef MOE_EXP_REL
+  if (MODE != MODE_L1) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+#endif
   block_barrier();   // every wavefront is done reading the operand stages
 
   if (next.idx >= 0) next.rec = make_uniform(raw_rec);

@@ -45,6 +45,74 @@ __global__ __launch_bounds__(256) void k_probe_mfma(float* out, int iters) {
   out[blockIdx.x * 256 + threadIdx.x] = sum;
 }
 
+// The MFMA loop again, now with the data movement of a GroupGEMM K step around it, so that the price of each kind of
+// traffic can be read off in TFLOP/s at the board's power limit: per 16 MFMAs of a wavefront (a half K step of the
+// 256 x 256 tile) optionally 8 ds_read_b128 that refresh the operand fragments from LDS (random bf16 data), 4
+// global -> LDS loads of 1 KiB (a workgroup's 16 KiB per half step, from a 2 MiB region that stays in the L2 -- or,
+// STREAM, one load in four from a region of 4 MiB per workgroup that is streamed through, i.e. from HBM), and a
+// workgroup barrier.  No wait depends on the loads except a bound on how many are in flight.
+template <bool LDS_READS, bool DMA, bool BARRIER, bool STREAM>
+__global__ __launch_bounds__(256, 1) void k_probe_mix(const char* __restrict__ gsrc, float* out, int iters) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];   // 64 KiB of operand data + 32 KiB landing zone
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  uint32_t s = 12345u + tid * 2654435761u + blockIdx.x * 40503u;
+  for (int i = tid; i < 96 * 1024 / 4; i += 256) {
+    s = s * 1664525u + 1013904223u;
+    const __bf16 lo = (__bf16)(((s >> 8) & 0xffff) / 65536.0f - 0.5f);
+    s = s * 1664525u + 1013904223u;
+    const __bf16 hi = (__bf16)(((s >> 8) & 0xffff) / 65536.0f - 0.5f);
+    ((uint32_t*)smem)[i] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+  }
+  __syncthreads();
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
+  auto lds_frag = [](uint32_t a) { return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a; };
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    a[i] = lds_frag(lds0 + (w * 8 + i) * 1024 + lane * 16);
+    b[i] = lds_frag(lds0 + (w * 8 + 4 + i) * 1024 + lane * 16);
+  }
+  f32x16 c[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) c[i][j] = (f32x16){0};
+  const uint32_t rd = lds0 + w * 16384 + lane * 16;      // the wavefront reads its own quarter of the operand data
+  const uint32_t land = lds0 + 65536 + w * 8192;          // and lands its loads in its own 8 KiB
+  const uint32_t goff = (uint32_t)(blockIdx.x & 31) * 65536u + w * 16384 + lane * 16;
+  const char* stream_base = gsrc + ((size_t)4 << 20) + (size_t)blockIdx.x * ((size_t)4 << 20);
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int m = 0; m < 16; m++) {
+      const int i = m >> 2, j = m & 3;
+      c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], c[i][j], 0, 0, 0);
+      if (LDS_READS && (m & 1) == 0) {
+        const int which = m >> 1;
+        const bf16x8 v = lds_frag(rd + ((it * 8 + which) & 15) * 1024);
+        if (which < 4) a[which] = v; else b[which - 4] = v;
+      }
+      if (DMA && (m & 3) == 0) {
+        const int q = m >> 2;
+        const char* base = (STREAM && q == 0) ? stream_base : gsrc + (size_t)((it & 3) * 4096);
+        const uint32_t off = (STREAM && q == 0) ? (uint32_t)((it * 4096) & ((4 << 20) - 1)) + w * 1024 + lane * 16 : goff + q * 1024;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(land + q * 1024)
+                     : "memory");
+      }
+    }
+    if (DMA) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+    if (BARRIER) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int t = 0; t < 16; t++) sum += c[i][j][t];
+  out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
 __global__ __launch_bounds__(256) void k_probe_copy(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
@@ -100,6 +168,44 @@ int moe_probe_mfma(int32_t random_data, int32_t iters, void* scratch, size_t scr
     else hipLaunchKernelGGL(k_probe_mfma<false>, dim3(n_cu), dim3(256), 0, st, out, iters);
   });
   if (ms <= 0.f) return MOE_ERR_HIP;
+  const double flop = (double)n_cu * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
+  *tflops = (float)(flop / (ms * 1e-3) / 1e12);
+  return MOE_OK;
+}
+
+int moe_probe_mix(int32_t mode, int32_t iters, void* scratch, size_t scratch_bytes, float* tflops, void* hip_stream) {
+  if (!scratch || !tflops || iters < 1 || iters > (1 << 22) || mode < 0 || mode > 15 || ((uintptr_t)scratch & 15))
+    return MOE_ERR_INVALID_ARG;
+  const bool lds = mode & 1, dma = mode & 2, bar = mode & 4, stream = mode & 8;
+  if (stream && !dma) return MOE_ERR_INVALID_ARG;
+  const int n_cu = compute_units();
+  if (n_cu <= 0) return MOE_ERR_HIP;
+  // layout of scratch: 4 MiB that the L2-resident loads read, then (streaming only) 4 MiB per workgroup; the
+  // results land at the start of the first region's last MiB, which no load reads
+  const size_t need = ((size_t)4 << 20) + (stream ? (size_t)n_cu * ((size_t)4 << 20) : 0);
+  if (scratch_bytes < need) return MOE_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const char* g = (const char*)scratch;
+  float* out = (float*)((char*)scratch + ((size_t)3 << 20));
+  constexpr int lds_bytes = 96 * 1024;
+  auto launch = [&](auto kern) -> hipError_t {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(n_cu), dim3(256), lds_bytes, st, g, out, iters);
+    return hipGetLastError();
+  };
+  hipError_t err = hipSuccess;
+  const float ms = timed(st, 1, [&] {
+    hipError_t e;
+    if (!lds && !dma) e = bar ? launch(k_probe_mix<false, false, true, false>) : launch(k_probe_mix<false, false, false, false>);
+    else if (lds && !dma) e = bar ? launch(k_probe_mix<true, false, true, false>) : launch(k_probe_mix<true, false, false, false>);
+    else if (!lds && dma && !stream) e = bar ? launch(k_probe_mix<false, true, true, false>) : launch(k_probe_mix<false, true, false, false>);
+    else if (lds && dma && !stream) e = bar ? launch(k_probe_mix<true, true, true, false>) : launch(k_probe_mix<true, true, false, false>);
+    else if (!lds) e = bar ? launch(k_probe_mix<false, true, true, true>) : launch(k_probe_mix<false, true, false, true>);
+    else e = bar ? launch(k_probe_mix<true, true, true, true>) : launch(k_probe_mix<true, true, false, true>);
+    if (e != hipSuccess) err = e;
+  });
+  if (err != hipSuccess || ms <= 0.f) return MOE_ERR_HIP;
   const double flop = (double)n_cu * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
   *tflops = (float)(flop / (ms * 1e-3) / 1e12);
   return MOE_OK;

@@ -1,0 +1,51 @@
+"""What each kind of data movement of a GroupGEMM K step costs at the board's power limit.
+
+Runs the library's probe kernels (moe_probe_mfma, moe_probe_mix): the register-only MFMA loop the GroupGEMM is built
+from, then the same loop with LDS fragment reads, global->LDS loads (L2-resident or with a quarter of them streaming
+from HBM) and a workgroup barrier added at the rates of the 256 x 256 tile.  Every line is a power-limited rate: the
+matrix pipes are busy all the time, so TFLOP/s follows the clock the board can hold with that mix.
+
+    python -m paper_2502_19811_amd.traffic_probe
+"""
+from __future__ import annotations
+
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+
+def main() -> int:
+    import torch
+
+    import paper_2502_19811_amd as moe
+
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    scratch = torch.randint(0, 255, ((n_cu + 1) * (4 << 20),), dtype=torch.uint8, device="cuda")
+    # random bytes are not all finite bf16 values: overwrite with a small-valued bf16 pattern
+    scratch.view(torch.bfloat16).copy_(torch.rand(scratch.numel() // 2, device="cuda", dtype=torch.float32).sub_(0.5)
+                                       .to(torch.bfloat16))
+    iters = 400000
+    rows = [("MFMA loop, zeros", lambda: moe.moe_probe_mfma(False, iters // 4, scratch)),
+            ("MFMA loop, random bf16", lambda: moe.moe_probe_mfma(True, iters // 4, scratch)),
+            ("mix 0: MFMA only (random bf16 from LDS)", lambda: moe.moe_probe_mix(0, iters, scratch)),
+            ("mix 1: + LDS fragment reads", lambda: moe.moe_probe_mix(1, iters, scratch)),
+            ("mix 3: + global->LDS loads, L2-resident", lambda: moe.moe_probe_mix(3, iters, scratch)),
+            ("mix 7: + workgroup barrier per half step", lambda: moe.moe_probe_mix(7, iters, scratch)),
+            ("mix 11: loads with a quarter from HBM, no barrier", lambda: moe.moe_probe_mix(11, iters, scratch)),
+            ("mix 15: everything", lambda: moe.moe_probe_mix(15, iters, scratch)),
+            ("MFMA loop, random bf16 (again)", lambda: moe.moe_probe_mfma(True, iters // 4, scratch))]
+    print("| loop | TFLOP/s | of the random-data MFMA loop |")
+    print("|---|---|---|")
+    base = None
+    for name, fn in rows:
+        v = fn()
+        if name.startswith("MFMA loop, random") and base is None:
+            base = v
+        print(f"| {name} | {v:.0f} | {v / base:.3f} |" if base else f"| {name} | {v:.0f} | |", flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -204,6 +204,12 @@ def test_device_probes_report_plausible_ceilings():
     gbps = moe.moe_probe_copy(dst, src)
     print(f"copy: {gbps:.0f} GB/s", flush=True)
     assert torch.equal(dst, src) and 500.0 < gbps < 8000.0
+    big = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+    mix = moe.moe_probe_mix(7, 4000, big)                       # LDS reads, L2-resident loads, barrier
+    print(f"mfma loop with a K step's data movement: {mix:.0f} TFLOP/s", flush=True)
+    assert 300.0 < mix < 2600.0
+    with pytest.raises(moe.MoEError):
+        moe.moe_probe_mix(15, 4000, big)                        # streaming needs 4 MiB per compute unit
     with pytest.raises(moe.MoEError):
         moe.moe_probe_mfma(True, 0, scratch)
     with pytest.raises(moe.MoEError):
