@@ -97,6 +97,14 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  finding them in the Infinity Cache)
  *   "weights_packed" 1: the W1 / W2 arguments of moe_layer_forward are buffers written by moe_pack_weights
  *                  (default 0: the plain row-major weights)
+ *   "handoff_fences" 1: measurement aid (results unchanged): every layer0 tile ends with an agent-scope release and
+ *                  every layer1 tile starts with an agent-scope acquire, the fences a tile-granular hand-off of h
+ *                  between the two GroupGEMMs inside one launch would need on a part with one L2 per XCD; the time
+ *                  difference against the normal run is the price of such a hand-off (default 0)
+ *   "alias_experts" 1: MEASUREMENT AID, RESULTS ARE WRONG ON PURPOSE: with plain (not packed) weights every expert
+ *                  reads expert 0's W1 / W2, so the weight stream of the GroupGEMMs stays cache-resident while every
+ *                  other access is unchanged and in bounds; the time difference against the normal run is what
+ *                  streaming the weights from HBM costs (default 0)
  *   "large_schedule" 1: build the tile schedules with the one-workgroup kernel that has no limit on the
  *                  number of M-tiles (the default picks it only above 2048 tiles); its orders are simpler
  *                  (less operand sharing inside an XCD), the results are the same bit for bit

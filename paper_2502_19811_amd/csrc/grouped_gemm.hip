@@ -491,9 +491,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       }
     }
   }
-#ifdef MOE_EXP_ACQ
-  if (MODE == MODE_L1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
+  // Measurement aid: the fences a tile-granular hand-off between the two GroupGEMMs would need (a layer1 tile
+  // acquiring what layer0 tiles on other XCDs released), without the hand-off itself.
+  if (MODE == MODE_L1 && p.handoff_fences) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   // address set-up and the first loads (A blocks 0..2, B stages 0..2)
   LoadState ls;
   setup_and_issue<WM, MT, NT, MODE, PK>(p, lds0, cur, ls, lane, w, !cur.pre);
@@ -674,9 +674,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     publish_panel(p, pending_panel);
     pending_panel = -1;
   }
-#ifdef MOE_EXP_REL
-  if (MODE != MODE_L1) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-#endif
+  if (MODE != MODE_L1 && p.handoff_fences) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the previous tile's stores
   block_barrier();   // every wavefront is done reading the operand stages
 
   if (next.idx >= 0) next.rec = make_uniform(raw_rec);

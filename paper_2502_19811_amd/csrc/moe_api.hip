@@ -41,6 +41,8 @@ struct moe_plan {
   int32_t max_tiles;
   int32_t large_schedule;  // 1: always the one-workgroup schedule builder
   int32_t block_m;         // M-tiles per block of the locality order
+  int32_t handoff_fences;  // measurement aid: per-tile release / acquire fences in the GroupGEMMs
+  int32_t alias_experts;   // measurement aid: every expert reads expert 0's weights (plain layout only)
   int32_t weights_packed;  // 1: W1 / W2 of a forward are in the layout moe_pack_weights writes
   int32_t serial;          // number of the last forward (tags the out-of-range report in the status words)
   int32_t n_tiles_n0, n_tiles_n1;
@@ -259,6 +261,16 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     p->weights_packed = (int32_t)v;
     return MOE_OK;
   }
+  if (!strcmp(key, "handoff_fences")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->handoff_fences = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "alias_experts")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->alias_experts = (int32_t)v;
+    return MOE_OK;
+  }
   if (!strcmp(key, "profile")) {
     if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
     if (v == 1 && !p->ev_created) {
@@ -291,6 +303,8 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   else if (!strcmp(key, "large_schedule")) *v = p->large_schedule;
   else if (!strcmp(key, "block_m")) *v = p->block_m;
   else if (!strcmp(key, "weights_packed")) *v = p->weights_packed;
+  else if (!strcmp(key, "alias_experts")) *v = p->alias_experts;
+  else if (!strcmp(key, "handoff_fences")) *v = p->handoff_fences;
   else return MOE_ERR_INVALID_ARG;
   return MOE_OK;
 }
@@ -388,6 +402,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   g.T = s.T;
   g.k = s.k;
   g.H = s.H;
+  g.handoff_fences = p->handoff_fences;
 
   if (p->phases & 2) {
     GemmParams a = g;
@@ -398,6 +413,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     a.b_expert_bytes = (uint64_t)s.H * s.F1 * 2;
     a.ldb = (uint32_t)s.F1;
     a.b_packed = p->weights_packed;
+    if (p->alias_experts && !p->weights_packed) a.b_expert_bytes = 0;   // measurement aid, see the option
     a.n_tiles_n = p->n_tiles_n0;
     a.C = ws.h;
     a.ldc = (uint32_t)s.F;
@@ -434,6 +450,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     b.b_expert_bytes = (uint64_t)s.F * s.H * 2;
     b.ldb = (uint32_t)s.H;
     b.b_packed = p->weights_packed;
+    if (p->alias_experts && !p->weights_packed) b.b_expert_bytes = 0;
     b.n_tiles_n = p->n_tiles_n1;
     b.C = ws.Y;
     b.ldc = (uint32_t)s.H;

@@ -84,6 +84,7 @@ struct GemmParams {
   uint32_t ldb;             // elements per row of B
   int32_t b_packed;         // 1: B is in the packed layout of moe_pack_weights (b_expert_bytes and ldb unused)
   int32_t n_tiles_n;        // column tiles of this layer (addressing of packed B)
+  int32_t handoff_fences;   // measurement aid: per-tile agent-scope release (layer0) / acquire (layer1)
   uint16_t* C;              // h (layer0) or Y (layer1)
   uint32_t ldc;             // elements per row of C
   int32_t K;                // reduction length

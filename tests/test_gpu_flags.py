@@ -191,6 +191,25 @@ def test_few_workgroups_walk_many_flagged_tiles(order):
     np.testing.assert_array_equal(run.out, base.out)
 
 
+def test_measurement_options_do_what_they_say():
+    """handoff_fences only adds memory fences (same bits); alias_experts makes every expert compute with expert 0's
+    weights (checked against the oracle fed with those weights)."""
+    H, cfg, inp, ids, w, layer = _setup()
+    layer.forward(); base = layer.results(); layer.close()
+    _, _, _, _, _, fenced = _setup({"handoff_fences": 1})
+    fenced.forward(); r1 = fenced.results(); fenced.close()
+    assert r1.status == 0
+    np.testing.assert_array_equal(r1.out, base.out)
+    _, _, _, _, _, aliased = _setup({"alias_experts": 1})
+    aliased.forward(); r2 = aliased.results(); aliased.close()
+    assert r2.status == 0
+    W1a = np.ascontiguousarray(np.broadcast_to(inp.W1[:1], inp.W1.shape))
+    W2a = np.ascontiguousarray(np.broadcast_to(inp.W2[:1], inp.W2.shape))
+    a, b = H.error_metrics(r2.out, orc.moe_layer(inp.x, W1a, W2a, ids, w, cfg.act))
+    assert a <= H.REL_TOL and b <= H.REL_TOL
+    np.testing.assert_array_equal(r2.perm, base.perm)
+
+
 def test_device_probes_report_plausible_ceilings():
     import torch
     import paper_2502_19811_amd as moe
