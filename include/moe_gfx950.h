@@ -97,6 +97,13 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  finding them in the Infinity Cache)
  *   "weights_packed" 1: the W1 / W2 arguments of moe_layer_forward are buffers written by moe_pack_weights
  *                  (default 0: the plain row-major weights)
+ *   "fuse_layers"  1: layer0 and layer1 run in one persistent launch (the pipelining between the two GroupGEMMs of
+ *                  Fig. 3/4 without a kernel boundary): a workgroup counts the layer0 tiles it finishes per M-tile,
+ *                  publishes the counts every "publish_every" tiles (default 16) behind one device-wide release, and
+ *                  a layer1 tile starts once all layer0 column tiles of its M-tile are published.  Same bits.  Used
+ *                  with the separate combine kernel and up to 2048 M-tiles; otherwise, and by default (0), the two
+ *                  launches.  Needs every workgroup of the launch resident at once: leave compute units free with
+ *                  "n_cu" for anything that runs beside the forward
  *   "handoff_fences" 1: measurement aid (results unchanged): every layer0 tile ends with an agent-scope release and
  *                  every layer1 tile starts with an agent-scope acquire, the fences a tile-granular hand-off of h
  *                  between the two GroupGEMMs inside one launch would need on a part with one L2 per XCD; the time

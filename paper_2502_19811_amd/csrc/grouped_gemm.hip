@@ -681,7 +681,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // early start of the successor (see above): its gather rows are requested now, its first loads after the first
   // 32-row block of the epilogue, into LDS the epilogue does not use
   bool do_pre = false;
-  if (kCanPre && next.idx >= 0 && next.rec.kind == kKind && ((ready_mask >> (next.rec.ready_seg & 63)) & 1)) do_pre = true;
+  if (kCanPre && !p.no_pre && next.idx >= 0 && next.rec.kind == kKind && ((ready_mask >> (next.rec.ready_seg & 63)) & 1)) do_pre = true;
   next.pre = do_pre;
   if (kCanPre && do_pre) load_arows<MODE>(p, next, lane, w);
 
@@ -846,6 +846,158 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     }
     combine_loop(p, &lds_slot[1], p.batch_publish != 0);
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Both GroupGEMMs in one persistent launch (the pipelining between the layers of Fig. 3/4 without a kernel boundary
+// in between).  A workgroup first walks the layer0 queues exactly as k_group_gemm does, counting its finished tiles
+// per M-tile in LDS; every publish_every tiles, and when the layer0 queues are used up, it makes its stores visible
+// device-wide (one agent-scope release for all tiles since the last one: a release per tile would cost a tenth of
+// layer0) and adds its counts to tile_done[].  It then walks the layer1 queues; a layer1 tile of M-tile m starts once
+// tile_done[m] has reached the number of layer0 column tiles.  No deadlock: a workgroup only reaches layer1 after
+// every layer0 item has been handed out, and the workgroups holding them wait for nothing but the ready flags (a
+// bounded wait).  Once a workgroup has seen every workgroup finish layer0 it stops checking, and only then lets a
+// tile start its successor's loads early.
+// ---------------------------------------------------------------------------------------------
+template <int MODE0, bool PK>
+__global__ __launch_bounds__(256, 1) void k_fused_layers(GemmParams p0, GemmParams p1, FuseParams f) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int32_t lds_slot[2];
+  __shared__ uint32_t lds_mask[2];
+  __shared__ int32_t lds_panel_count[kMaxPanels];      // unused here; run_tile takes it
+  __shared__ int32_t lds_tile_cnt[kScheduleTileCap];   // layer0 tiles this workgroup finished per M-tile, not yet published
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kScheduleTileCap; i += 256) lds_tile_cnt[i] = 0;
+  for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
+  const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int xcd = blockIdx.x & (kXcds - 1);
+  const int n_tiles = min(*p0.n_tiles, (int)kScheduleTileCap);
+  int pending_panel = -1;
+  __syncthreads();
+
+  auto take_sync = [&](const GemmParams& p, const Queue& q, Tile& t, auto mode) {
+    constexpr int MODE = decltype(mode)::value;
+    if (tid == 0) {
+      int idx = take_from(p, xcd, q.own_len, q.own_base);
+      if (idx < 0) idx = steal(p, xcd);
+      lds_slot[0] = idx;
+    }
+    __syncthreads();
+    t.idx = uniform((int)lds_slot[0]);
+    t.pre = 0;
+    __syncthreads();
+    if (t.idx >= 0) {
+      t.rec = load_item(p, t.idx);
+      load_arows<MODE>(p, t, lane, w);
+    }
+  };
+  // all stores of this workgroup so far become visible device-wide, then its counts are added
+  auto publish = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    for (int i = tid; i < n_tiles; i += 256) {
+      const int c = lds_tile_cnt[i];
+      if (c > 0) {
+        __hip_atomic_fetch_add(&f.tile_done[i], (uint32_t)c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lds_tile_cnt[i] = 0;
+      }
+    }
+    __syncthreads();
+  };
+
+  // ---- layer0
+  {
+    using M0 = std::integral_constant<int, MODE0>;
+    Queue q;
+    q.own_len = p0.queue_len[xcd];
+    q.own_base = queue_pos(p0, xcd, 0);
+    Tile cur, next;
+    int since_publish = 0;
+    take_sync(p0, q, cur, M0{});
+    while (cur.idx >= 0) {
+      __syncthreads();
+      if (!cur.pre && !segment_ready<MODE0>(p0, cur, lds_slot, true)) {
+        take_sync(p0, q, cur, M0{});   // timed out (status says so): the tile is given up
+        continue;
+      }
+      next.idx = -1;
+      const int m_tile = cur.rec.m_tile;
+      if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE0, PK>(p0, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+      else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE0, PK>(p0, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+      else run_tile<1, 2, 2, MODE0, PK>(p0, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+      if (tid == 0 && (unsigned)m_tile < (unsigned)kScheduleTileCap) lds_tile_cnt[m_tile] += 1;
+      cur = next;
+      if (++since_publish >= f.publish_every && cur.idx >= 0) {
+        // (if the successor's first loads are already in flight the fence waits for them too; the tile code's own
+        // waits then find them done)
+        publish();
+        since_publish = 0;
+      }
+    }
+    __syncthreads();
+    publish();
+    if (tid == 0) __hip_atomic_fetch_add(f.wgs_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // ---- layer1
+  {
+    using M1 = std::integral_constant<int, MODE_L1>;
+    if ((int)blockIdx.x >= p1.n_mfma) return;
+    GemmParams q1 = p1;
+    q1.no_pre = 1;
+    bool all_seen = false;
+    Queue q;
+    q.own_len = q1.queue_len[xcd];
+    q.own_base = queue_pos(q1, xcd, 0);
+    Tile cur, next;
+    take_sync(q1, q, cur, M1{});
+    while (cur.idx >= 0) {
+      __syncthreads();
+      if (!all_seen) {
+        // the rows of this M-tile: wait until every layer0 column tile of it has been published
+        if (tid == 0) {
+          const uint32_t m = (uint32_t)cur.rec.m_tile < (uint32_t)kScheduleTileCap ? (uint32_t)cur.rec.m_tile : 0u;
+          bool ok = spin_until_ge(&f.tile_done[m], (uint32_t)f.n_tiles_n0, q1.spin_limit ? q1.spin_limit : (1u << 26));
+          if (!ok) atomicExch(q1.status, (int)MOE_ERR_TIMEOUT);
+          const uint32_t done = __hip_atomic_load(f.wgs_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          lds_slot[1] = (ok ? 1 : 0) | (done >= gridDim.x ? 2 : 0);
+        }
+        __syncthreads();
+        const int st = lds_slot[1];
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (!(st & 1)) {
+          take_sync(q1, q, cur, M1{});   // timed out: give the tile up
+          continue;
+        }
+        if (st & 2) {
+          all_seen = true;     // every workgroup has published everything: nothing left to wait for
+          q1.no_pre = 0;
+        }
+      }
+      next.idx = -1;
+      if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE_L1, PK>(q1, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+      else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE_L1, PK>(q1, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+      else run_tile<1, 2, 2, MODE_L1, PK>(q1, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+      cur = next;
+    }
+  }
+}
+
+template <int MODE0, bool PK>
+static hipError_t launch_fused(const GemmParams& p0, const GemmParams& p1, const FuseParams& f, int grid, hipStream_t st) {
+  constexpr int lds = kLdsBytes;
+  auto kern = k_fused_layers<MODE0, PK>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p0, p1, f);
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_layers(const GemmParams& p0, const GemmParams& p1, const FuseParams& f, int act, int grid, hipStream_t st) {
+  if (act == MOE_ACT_SWIGLU)
+    return p0.b_packed ? launch_fused<MODE_L0_SWIGLU, true>(p0, p1, f, grid, st) : launch_fused<MODE_L0_SWIGLU, false>(p0, p1, f, grid, st);
+  return p0.b_packed ? launch_fused<MODE_L0_GELU, true>(p0, p1, f, grid, st) : launch_fused<MODE_L0_GELU, false>(p0, p1, f, grid, st);
 }
 
 template <int MODE, bool PK>

@@ -183,6 +183,7 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
     }
     if (threadIdx.x < 2 * kXcds) p.ws.status[8 + threadIdx.x] = 0;   // queue heads of both layers
     for (int i = threadIdx.x; i < p.n_tiles_n1; i += 256) p.ws.panel_done[i] = 0;
+    for (int i = threadIdx.x; i < p.max_tiles + 1; i += 256) p.ws.tile_done[i] = 0;
     if (e < E) {
       p.ws.counts[e] = my_cnt;
       p.ws.offsets[e] = off[e];
@@ -778,8 +779,9 @@ hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalPa
 
 // Queue heads, combine counter, panel counters and the status word back to zero: what the scatter kernel does at the
 // start of a forward, for a forward that runs the schedules of an earlier index build again.
-__global__ void k_reset_counters(Workspace ws, int n_tiles_n1) {
+__global__ void k_reset_counters(Workspace ws, int n_tiles_n1, int max_tiles) {
   const int t = threadIdx.x;
+  for (int i = t; i < max_tiles + 1; i += 256) ws.tile_done[i] = 0;
   if (t == 0) {
     ws.status[0] = 0;
     ws.status[4] = 0;
@@ -788,8 +790,8 @@ __global__ void k_reset_counters(Workspace ws, int n_tiles_n1) {
   for (int i = t; i < n_tiles_n1; i += 256) ws.panel_done[i] = 0;
 }
 
-hipError_t launch_reset_counters(const Workspace& ws, int n_tiles_n1, hipStream_t st) {
-  hipLaunchKernelGGL(k_reset_counters, dim3(1), dim3(256), 0, st, ws, n_tiles_n1);
+hipError_t launch_reset_counters(const Workspace& ws, int n_tiles_n1, int max_tiles, hipStream_t st) {
+  hipLaunchKernelGGL(k_reset_counters, dim3(1), dim3(256), 0, st, ws, n_tiles_n1, max_tiles);
   return hipGetLastError();
 }
 

@@ -41,13 +41,15 @@ struct moe_plan {
   int32_t max_tiles;
   int32_t large_schedule;  // 1: always the one-workgroup schedule builder
   int32_t block_m;         // M-tiles per block of the locality order
+  int32_t fuse_layers;     // 1: both GroupGEMMs in one launch, layer1 tiles waiting on per-M-tile counters
+  int32_t publish_every;   // one-launch variant: layer0 tiles between two publications of a workgroup
   int32_t handoff_fences;  // measurement aid: per-tile release / acquire fences in the GroupGEMMs
   int32_t alias_experts;   // measurement aid: every expert reads expert 0's weights (plain layout only)
   int32_t weights_packed;  // 1: W1 / W2 of a forward are in the layout moe_pack_weights writes
   int32_t serial;          // number of the last forward (tags the out-of-range report in the status words)
   int32_t n_tiles_n0, n_tiles_n1;
   size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
-      off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_h, off_Y, total_bytes;
+      off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_tile_done, off_h, off_Y, total_bytes;
 };
 
 namespace {
@@ -83,6 +85,7 @@ void layout(moe_plan* p) {
   p->off_items0 = take((size_t)p->max_tiles * p->n_tiles_n0 * sizeof(ItemRec));
   p->off_items1 = take((size_t)(p->max_tiles + 3 * kXcds) * p->n_tiles_n1 * sizeof(ItemRec));
   p->off_panel_done = take((size_t)p->n_tiles_n1 * 4);
+  p->off_tile_done = take((size_t)(p->max_tiles + 1) * 4);
   p->off_h = take((size_t)s.R * s.F * 2);
   p->off_Y = take((size_t)s.R * s.H * 2);
   p->total_bytes = o;
@@ -107,6 +110,7 @@ Workspace view(const moe_plan* p, void* base) {
   w.items0 = (ItemRec*)(b + p->off_items0);
   w.items1 = (ItemRec*)(b + p->off_items1);
   w.panel_done = (uint32_t*)(b + p->off_panel_done);
+  w.tile_done = (uint32_t*)(b + p->off_tile_done);
   w.h = (uint16_t*)(b + p->off_h);
   w.Y = (uint16_t*)(b + p->off_Y);
   return w;
@@ -182,6 +186,7 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
   p->layer1_order = 0;   // measured faster on every workload so far: see the sweep tool and default_n_dm
   p->serial = 0x2545F491;   // arbitrary start: an uninitialised workspace word is unlikely to match it
   p->block_m = 4;        // measured: 2-4 % faster on layer1 than 8, see the header
+  p->publish_every = 16;
   p->spin_limit = 1 << 26;   // about 20 s of polling: a lost flag ends in MOE_ERR_TIMEOUT, not in a hung GPU
   p->phases = 15;
   p->n_cu = 0;
@@ -261,6 +266,16 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     p->weights_packed = (int32_t)v;
     return MOE_OK;
   }
+  if (!strcmp(key, "fuse_layers")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->fuse_layers = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "publish_every")) {
+    if (v < 1 || v > 1 << 20) return MOE_ERR_INVALID_ARG;
+    p->publish_every = (int32_t)v;
+    return MOE_OK;
+  }
   if (!strcmp(key, "handoff_fences")) {
     if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
     p->handoff_fences = (int32_t)v;
@@ -305,6 +320,8 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   else if (!strcmp(key, "weights_packed")) *v = p->weights_packed;
   else if (!strcmp(key, "alias_experts")) *v = p->alias_experts;
   else if (!strcmp(key, "handoff_fences")) *v = p->handoff_fences;
+  else if (!strcmp(key, "fuse_layers")) *v = p->fuse_layers;
+  else if (!strcmp(key, "publish_every")) *v = p->publish_every;
   else return MOE_ERR_INVALID_ARG;
   return MOE_OK;
 }
@@ -383,7 +400,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     if (launch_index_build(ip, st) != hipSuccess) return MOE_ERR_HIP;
   } else {
     // the schedules of the last index build on this workspace are run again: their queue heads and counters start over
-    if (launch_reset_counters(ws, p->n_tiles_n1, st) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_reset_counters(ws, p->n_tiles_n1, p->max_tiles, st) != hipSuccess) return MOE_ERR_HIP;
   }
 
   if (!mark(1)) return MOE_ERR_HIP;
@@ -404,76 +421,89 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   g.H = s.H;
   g.handoff_fences = p->handoff_fences;
 
-  if (p->phases & 2) {
-    GemmParams a = g;
-    a.A = (const char*)x;
-    a.lda_bytes = (uint32_t)s.H * 2;
-    a.a_rows = ws.row_token;
-    a.B = (const char*)W1;
-    a.b_expert_bytes = (uint64_t)s.H * s.F1 * 2;
-    a.ldb = (uint32_t)s.F1;
-    a.b_packed = p->weights_packed;
-    if (p->alias_experts && !p->weights_packed) a.b_expert_bytes = 0;   // measurement aid, see the option
-    a.n_tiles_n = p->n_tiles_n0;
-    a.C = ws.h;
-    a.ldc = (uint32_t)s.F;
-    a.K = s.H;
-    a.items = ws.items0;
-    a.seg_ready = seg_ready;
-    a.ready_epoch = ready_epoch;
-    a.n_segments = s.S;
-    // no more workgroups than there can be items (small batches are bound by the launch, not by the work)
-    const int64_t max_items0 = (int64_t)p->max_tiles * p->n_tiles_n0;
-    const int grid0 = max_items0 < p->n_cu ? (max_items0 < 8 ? 8 : (int)max_items0) : p->n_cu;
-    a.n_mfma = grid0;
-    a.queue_heads = ws.status + 8;
-    a.queue_len = ws.status + 24;
-    if (order0 != 1 && !large) {
-      a.queue_base = ws.status + 48;   // contiguous per-XCD queues (locality order)
-      a.queue_stride = 1;
-    } else {
-      a.queue_base = nullptr;          // queue x = list positions x, x + 8, ...
-      a.queue_stride = kXcds;
-    }
-    if (launch_layer0(a, s.act, grid0, st) != hipSuccess) return MOE_ERR_HIP;
+  const bool fused = p->layer1_order == 1 && (p->phases & 8);   // top-k reduction inside the layer1 kernel
+  // both GroupGEMMs in one launch (only with the separate combine kernel and the LDS-resident schedule builder's
+  // tile count, which bounds the per-workgroup tile counters)
+  const bool one_launch = p->fuse_layers && (p->phases & 2) && (p->phases & 4) && !fused && !large;
+
+  GemmParams a = g;
+  a.A = (const char*)x;
+  a.lda_bytes = (uint32_t)s.H * 2;
+  a.a_rows = ws.row_token;
+  a.B = (const char*)W1;
+  a.b_expert_bytes = (uint64_t)s.H * s.F1 * 2;
+  a.ldb = (uint32_t)s.F1;
+  a.b_packed = p->weights_packed;
+  if (p->alias_experts && !p->weights_packed) a.b_expert_bytes = 0;   // measurement aid, see the option
+  a.n_tiles_n = p->n_tiles_n0;
+  a.C = ws.h;
+  a.ldc = (uint32_t)s.F;
+  a.K = s.H;
+  a.items = ws.items0;
+  a.seg_ready = seg_ready;
+  a.ready_epoch = ready_epoch;
+  a.n_segments = s.S;
+  // no more workgroups than there can be items (small batches are bound by the launch, not by the work)
+  const int64_t max_items0 = (int64_t)p->max_tiles * p->n_tiles_n0;
+  const int grid0 = max_items0 < p->n_cu ? (max_items0 < 8 ? 8 : (int)max_items0) : p->n_cu;
+  a.n_mfma = grid0;
+  a.queue_heads = ws.status + 8;
+  a.queue_len = ws.status + 24;
+  if (order0 != 1 && !large) {
+    a.queue_base = ws.status + 48;   // contiguous per-XCD queues (locality order)
+    a.queue_stride = 1;
+  } else {
+    a.queue_base = nullptr;          // queue x = list positions x, x + 8, ...
+    a.queue_stride = kXcds;
   }
 
-  if (!mark(2)) return MOE_ERR_HIP;
+  GemmParams b = g;
+  b.A = (const char*)ws.h;
+  b.lda_bytes = (uint32_t)s.F * 2;
+  b.a_rows = nullptr;
+  b.B = (const char*)W2;
+  b.b_expert_bytes = (uint64_t)s.F * s.H * 2;
+  b.ldb = (uint32_t)s.H;
+  b.b_packed = p->weights_packed;
+  if (p->alias_experts && !p->weights_packed) b.b_expert_bytes = 0;
+  b.n_tiles_n = p->n_tiles_n1;
+  b.C = ws.Y;
+  b.ldc = (uint32_t)s.H;
+  b.K = s.F;
+  b.items = ws.items1;
+  b.panel_done = ws.panel_done;
+  int n_dm = fused ? (p->n_dm >= 0 ? p->n_dm : default_n_dm(s)) : 0;
+  if (n_dm > p->n_cu - 8) n_dm = p->n_cu - 8;
+  const int64_t max_items1 = (int64_t)p->max_tiles * p->n_tiles_n1;
+  int grid1 = p->n_cu;
+  if (!fused && max_items1 < grid1) grid1 = max_items1 < 8 ? 8 : (int)max_items1;
+  b.n_mfma = grid1 - n_dm;
+  b.fused_combine = fused ? 1 : 0;
+  b.batch_publish = (fused && n_dm == 0 && s.H / kTileN <= 128) ? 1 : 0;
+  b.inv_perm = ws.inv_perm;
+  b.topk_weights = topk_weights;
+  b.out = (uint16_t*)out;
+  b.combine_counter = ws.status + 4;
+  b.queue_heads = ws.status + 16;
+  b.queue_len = ws.status + 32;
+  b.queue_base = ws.status + 40;
+  b.queue_stride = 1;
 
-  const bool fused = p->layer1_order == 1 && (p->phases & 8);
-  if (p->phases & 4) {
-    GemmParams b = g;
-    b.A = (const char*)ws.h;
-    b.lda_bytes = (uint32_t)s.F * 2;
-    b.a_rows = nullptr;
-    b.B = (const char*)W2;
-    b.b_expert_bytes = (uint64_t)s.F * s.H * 2;
-    b.ldb = (uint32_t)s.H;
-    b.b_packed = p->weights_packed;
-    if (p->alias_experts && !p->weights_packed) b.b_expert_bytes = 0;
-    b.n_tiles_n = p->n_tiles_n1;
-    b.C = ws.Y;
-    b.ldc = (uint32_t)s.H;
-    b.K = s.F;
-    b.items = ws.items1;
-    b.panel_done = ws.panel_done;
-    int n_dm = fused ? (p->n_dm >= 0 ? p->n_dm : default_n_dm(s)) : 0;
-    if (n_dm > p->n_cu - 8) n_dm = p->n_cu - 8;
-    const int64_t max_items1 = (int64_t)p->max_tiles * p->n_tiles_n1;
-    int grid1 = p->n_cu;
-    if (!fused && max_items1 < grid1) grid1 = max_items1 < 8 ? 8 : (int)max_items1;
-    b.n_mfma = grid1 - n_dm;
-    b.fused_combine = fused ? 1 : 0;
-    b.batch_publish = (fused && n_dm == 0 && s.H / kTileN <= 128) ? 1 : 0;
-    b.inv_perm = ws.inv_perm;
-    b.topk_weights = topk_weights;
-    b.out = (uint16_t*)out;
-    b.combine_counter = ws.status + 4;
-    b.queue_heads = ws.status + 16;
-    b.queue_len = ws.status + 32;
-    b.queue_base = ws.status + 40;
-    b.queue_stride = 1;
-    if (launch_layer1(b, grid1, st) != hipSuccess) return MOE_ERR_HIP;
+  if (one_launch) {
+    FuseParams f;
+    f.tile_done = ws.tile_done;
+    f.wgs_done = ws.tile_done + p->max_tiles;
+    f.n_tiles_n0 = p->n_tiles_n0;
+    f.publish_every = p->publish_every;
+    const int grid = grid0 > grid1 ? grid0 : grid1;
+    a.n_mfma = grid;
+    b.n_mfma = grid;
+    if (launch_fused_layers(a, b, f, s.act, grid, st) != hipSuccess) return MOE_ERR_HIP;
+    if (!mark(2)) return MOE_ERR_HIP;   // the whole launch is booked as the layer0 phase
+  } else {
+    if ((p->phases & 2) && launch_layer0(a, s.act, grid0, st) != hipSuccess) return MOE_ERR_HIP;
+    if (!mark(2)) return MOE_ERR_HIP;
+    if ((p->phases & 4) && launch_layer1(b, grid1, st) != hipSuccess) return MOE_ERR_HIP;
   }
   if (!mark(3)) return MOE_ERR_HIP;
   if ((p->phases & 8) && !(fused && (p->phases & 4))) {

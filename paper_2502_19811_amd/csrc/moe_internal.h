@@ -50,6 +50,7 @@ struct Workspace {
   ItemRec* items0;        // [max_tiles * n_tiles_n0] layer0 schedule
   ItemRec* items1;        // [(max_tiles + 24) * n_tiles_n1] layer1 schedule, one contiguous queue per XCD
   uint32_t* panel_done;   // [n_tiles_n1] finished M-tiles per column panel of layer1
+  uint32_t* tile_done;    // [max_tiles + 1] one-launch variant: layer0 items finished per M-tile; last: workgroups done
   uint16_t* h;            // [R,F] bf16 activation buffer
   uint16_t* Y;            // [R,H] bf16 layer1 shared tensor
 };
@@ -85,6 +86,7 @@ struct GemmParams {
   int32_t b_packed;         // 1: B is in the packed layout of moe_pack_weights (b_expert_bytes and ldb unused)
   int32_t n_tiles_n;        // column tiles of this layer (addressing of packed B)
   int32_t handoff_fences;   // measurement aid: per-tile agent-scope release (layer0) / acquire (layer1)
+  int32_t no_pre;           // 1: a tile never starts its successor's loads early (the successor's rows may not be there)
   uint16_t* C;              // h (layer0) or Y (layer1)
   uint32_t ldc;             // elements per row of C
   int32_t K;                // reduction length
@@ -118,6 +120,14 @@ struct GemmParams {
   int32_t* combine_counter;
 };
 
+// The two GroupGEMMs in one launch: what the hand-over of h from layer0 tiles to layer1 tiles needs.
+struct FuseParams {
+  uint32_t* tile_done;      // [max_tiles] layer0 items finished (and published) per M-tile
+  uint32_t* wgs_done;       // [1] workgroups that have published all their layer0 tiles
+  int32_t n_tiles_n0;       // layer0 items per M-tile
+  int32_t publish_every;    // layer0 tiles between two publications of a workgroup
+};
+
 struct ArrivalParams {
   int32_t S;
   int32_t seg_offsets[kMaxSegments + 1];
@@ -140,9 +150,10 @@ struct CombineParams {
 // kernel launchers (defined in the .hip files)
 hipError_t launch_route_topk(const float* logits, int T, int E, int k, int32_t* ids, float* w, hipStream_t st);
 hipError_t launch_index_build(const IndexParams& p, hipStream_t st);
-hipError_t launch_reset_counters(const Workspace& ws, int n_tiles_n1, hipStream_t st);
+hipError_t launch_reset_counters(const Workspace& ws, int n_tiles_n1, int max_tiles, hipStream_t st);
 hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st);
 hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st);
+hipError_t launch_fused_layers(const GemmParams& p0, const GemmParams& p1, const FuseParams& f, int act, int grid, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);
 hipError_t launch_pack_weights(const void* B, void* out, int E, int K, int ldb, int n_tiles_n, int swiglu_F, hipStream_t st);
 hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalParams& a, int n_wg, hipStream_t st);

@@ -124,14 +124,16 @@ def test_full_size_token_reversal_moves_every_row_bit_for_bit(name):
 def test_full_size_variants_give_the_same_bits():
     """On the Mixtral-shaped workload, at full size: the in-kernel reduction of finished column panels with and without
     data-movement workgroups (16 panels, 32 token chunks each), the source-ordered layer0 schedule, the packed
-    weights and the 128-row tiling all give the default run's output bit for bit."""
+    weights, the 128-row tiling and the one-launch variant of the two GroupGEMMs all give the default run's output
+    bit for bit."""
     cfg = wl.CONFIGS["mixtral"]
     print("variants mixtral: generating inputs", flush=True)
     inp = wl.make_inputs(cfg, threads=16)
     ids, w = orc.route_topk(inp.logits, cfg.k)
     base = _run(cfg, inp, ids, w)
     for opts, packed in (({"layer1_order": 1, "n_dm": 16}, False), ({"layer1_order": 1, "n_dm": 0}, False),
-                         ({"layer0_order": 1}, False), ({}, True), ({"tile_m": 128}, False)):
+                         ({"layer0_order": 1}, False), ({}, True), ({"tile_m": 128}, False),
+                         ({"fuse_layers": 1, "spin_limit": 1 << 18}, True)):
         print(f"  options {opts} packed {packed}", flush=True)
         run = _run(cfg, inp, ids, w, opts, packed)
         np.testing.assert_array_equal(run.out, base.out)

@@ -87,6 +87,29 @@ def test_packed_weights_give_the_same_bits(H, cfg):
         np.testing.assert_array_equal(run.perm, base.perm)
 
 
+@pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
+def test_one_launch_for_both_groupgemms_gives_the_same_bits(H, cfg):
+    """Layer0 and layer1 in one persistent launch, layer1 tiles waiting on per-M-tile counters: same output bit for bit
+    as the two launches, for every tile height, with many and with few workgroups and with publication after every
+    tile.  The small spin limit turns a lost hand-over into an error within milliseconds instead of a long wait."""
+    print(f"one-launch case {cfg.name}", flush=True)
+    inp = wl.make_inputs(cfg, threads=4)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    for tile_m in (64, 128, 256):
+        two = H.GpuLayer(cfg, inp, ids, w, {"tile_m": tile_m})
+        two.forward(); base = two.results(); two.close()
+        for extra in ({}, {"n_cu": 8, "publish_every": 1}, {"n_cu": 16, "publish_every": 3}):
+            opts = dict(extra, tile_m=tile_m, fuse_layers=1, spin_limit=1 << 16)
+            print(f"  {opts}", flush=True)
+            one = H.GpuLayer(cfg, inp, ids, w, opts, packed=(tile_m == 128))
+            one.forward(); run = one.results()
+            assert run.status == 0
+            np.testing.assert_array_equal(run.out, base.out)
+            one.forward(); again = one.results(); one.close()      # counters start over on the same workspace
+            assert again.status == 0
+            np.testing.assert_array_equal(again.out, base.out)
+
+
 def test_router_matches_oracle(H):
     import paper_2502_19811_amd as moe
     for (T, E, k, seed) in [(128, 4, 2, 1), (513, 64, 8, 2), (100, 8, 8, 3), (77, 16, 1, 4), (64, 200, 6, 5)]:
