@@ -66,10 +66,14 @@ int moe_plan_destroy(moe_plan_t *plan);
 /* Tunables.  Keys:
  *   "tile_m"       64 / 128 / 256: rows of the tallest GroupGEMM tile (default: chosen from T*k/E)
  *   "n_dm"         data-movement workgroups of the layer1 kernel (default: table lookup per shape)
- *   "layer1_order" 1 = finished column panels (Fig. 6) are reduced inside the layer1 kernel, by its n_dm
- *                  data-movement workgroups and by GEMM workgroups that ran out of tiles;
- *                  0 = a separate combine kernel after the layer1 kernel (default: the faster one on
- *                  every workload measured, see paper_2502_19811_amd/split_sweep.py)
+ *   "layer1_order" where the top-k reduction runs: 0 = a separate combine kernel after the layer1 kernel (default:
+ *                  the fastest on every workload measured, see paper_2502_19811_amd/split_sweep.py);
+ *                  1 = finished column panels (Fig. 6) are reduced inside the layer1 kernel, by its n_dm
+ *                  data-movement workgroups and by GEMM workgroups that ran out of tiles (Section 3.2.1's
+ *                  specialised blocks); 2 = in the layer1 epilogue (the vertical fusion Section 3.2.1 weighs
+ *                  against them): a tile writes its rows of Y, announces each on a counter per token and column
+ *                  panel, and the row that arrives last of a token's k reduces that token.  All three give the
+ *                  same bits
  *   "layer0_order" order of the layer0 tiles: 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5:
  *                  M-tiles sorted by the segment they wait for, all column tiles of an M-tile in a row);
  *                  2 = waves: the S source segments are grouped into "layer0_waves" waves, the tiles are

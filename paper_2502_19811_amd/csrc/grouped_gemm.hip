@@ -777,6 +777,58 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       pending_panel = n_tile;
     }
   }
+  // Top-k reduction in the layer1 epilogue (the vertical fusion Section 3.2.1 weighs against its specialised
+  // blocks).  The k rows of a token lie in tiles of different experts, finished by different workgroups at different
+  // times, so the tile still writes its rows of Y; then every row announces itself on a counter per (token, column
+  // panel), and the row that finds the other k-1 already there reduces the token: it reads the k rows back in slot
+  // order and writes the output row -- the same sum in the same order as the stand-alone kernel, whoever comes last.
+  // Nobody waits for anybody; the price is one device-wide release per tile (the rows must be visible before they are
+  // announced) and one acquire.
+  if (MODE == MODE_L1 && p.epilogue_combine) {
+    volatile int32_t* last_list = (volatile int32_t*)(smem + staging_offset(BM));   // the staging area is free again
+    int32_t* last_count = (int32_t*)(smem + staging_offset(BM) + 256 * 4);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    if (tid == 0) *last_count = 0;
+    __syncthreads();
+    const int n_panels = p.H / BN;
+    if (tid < nrows) {
+      const int t = p.perm[row0 + tid] / p.k;
+      const uint32_t before = __hip_atomic_fetch_add(&p.arrive[(size_t)t * n_panels + n_tile], 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+      if (before + 1 == (uint32_t)p.k) last_list[atomicAdd(last_count, 1)] = t;
+    }
+    __syncthreads();
+    const int n_last = uniform(*(volatile int32_t*)last_count);
+    if (n_last > 0) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      const size_t col = (size_t)n_tile * BN + (tid & 31) * 8;
+      for (int e = tid >> 5; e < n_last; e += 8) {
+        const int t = last_list[e];
+        float acc[8];
+#pragma unroll
+        for (int c = 0; c < 8; c++) acc[c] = 0.f;
+        for (int j = 0; j < p.k; j++) {
+          const int row = p.inv_perm[t * p.k + j];
+          const float wj = p.topk_weights[t * p.k + j];
+          const u32x4 v = *(const u32x4*)(p.C + (size_t)row * p.ldc + col);
+#pragma unroll
+          for (int c = 0; c < 4; c++) {
+            acc[2 * c] += wj * __uint_as_float(v[c] << 16);
+            acc[2 * c + 1] += wj * __uint_as_float(v[c] & 0xffff0000u);
+          }
+        }
+        u32x4 o;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+          bf16x2 pr = {(__bf16)acc[2 * c], (__bf16)acc[2 * c + 1]};
+          o[c] = __builtin_bit_cast(uint32_t, pr);
+        }
+        *(u32x4*)(p.out + (size_t)t * p.H + col) = o;
+      }
+    }
+    __syncthreads();   // the list is read out before the next tile's epilogue reuses the staging area
+  }
   // rows of A the next tile gathers (requested only now: held across the epilogue they push it into spilling)
   if (next.idx >= 0 && !do_pre) load_arows<MODE>(p, next, lane, w);
 }
@@ -1096,6 +1148,18 @@ __global__ __launch_bounds__(256) void k_combine(CombineParams p) {
     }
     *(u32x4*)(p.out + (size_t)t * p.H + col) = o;
   }
+}
+
+__global__ __launch_bounds__(256) void k_zero_u32(uint32_t* __restrict__ ptr, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) ptr[i] = 0u;
+}
+
+hipError_t launch_zero_u32(uint32_t* ptr, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  size_t grid = (n + 255) / 256;
+  if (grid > 1024) grid = 1024;
+  hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)grid), dim3(256), 0, st, ptr, n);
+  return hipGetLastError();
 }
 
 hipError_t launch_combine(const CombineParams& p, hipStream_t st) {

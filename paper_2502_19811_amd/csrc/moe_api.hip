@@ -49,7 +49,7 @@ struct moe_plan {
   int32_t serial;          // number of the last forward (tags the out-of-range report in the status words)
   int32_t n_tiles_n0, n_tiles_n1;
   size_t off_status, off_counts, off_offsets, off_perm, off_inv_perm, off_row_token, off_block_hist, off_tile_expert,
-      off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_tile_done, off_h, off_Y, total_bytes;
+      off_tile_row0, off_tile_rows, off_tile_ready, off_tile_kind, off_tile_order, off_items0, off_items1, off_panel_done, off_tile_done, off_arrive, off_h, off_Y, total_bytes;
 };
 
 namespace {
@@ -86,6 +86,7 @@ void layout(moe_plan* p) {
   p->off_items1 = take((size_t)(p->max_tiles + 3 * kXcds) * p->n_tiles_n1 * sizeof(ItemRec));
   p->off_panel_done = take((size_t)p->n_tiles_n1 * 4);
   p->off_tile_done = take((size_t)(p->max_tiles + 1) * 4);
+  p->off_arrive = take((size_t)s.T * p->n_tiles_n1 * 4);
   p->off_h = take((size_t)s.R * s.F * 2);
   p->off_Y = take((size_t)s.R * s.H * 2);
   p->total_bytes = o;
@@ -111,6 +112,7 @@ Workspace view(const moe_plan* p, void* base) {
   w.items1 = (ItemRec*)(b + p->off_items1);
   w.panel_done = (uint32_t*)(b + p->off_panel_done);
   w.tile_done = (uint32_t*)(b + p->off_tile_done);
+  w.arrive = (uint32_t*)(b + p->off_arrive);
   w.h = (uint16_t*)(b + p->off_h);
   w.Y = (uint16_t*)(b + p->off_Y);
   return w;
@@ -232,7 +234,7 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
     return MOE_OK;
   }
   if (!strcmp(key, "layer1_order")) {
-    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    if (v < 0 || v > 2) return MOE_ERR_INVALID_ARG;
     p->layer1_order = (int32_t)v;
     return MOE_OK;
   }
@@ -391,7 +393,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     ip.n_tiles_n1 = p->n_tiles_n1;
     ip.layer0_order = order0;
     ip.layer0_waves = waves0;
-    ip.layer1_order = p->layer1_order;
+    ip.layer1_order = p->layer1_order == 1 ? 1 : 0;   // only the in-kernel panel reduction needs the panel-major order
     ip.max_tiles = p->max_tiles;
     ip.force_large_schedule = p->large_schedule;
     ip.block_m = p->block_m;
@@ -422,6 +424,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   g.handoff_fences = p->handoff_fences;
 
   const bool fused = p->layer1_order == 1 && (p->phases & 8);   // top-k reduction inside the layer1 kernel
+  const bool in_epilogue = p->layer1_order == 2 && (p->phases & 8) && (p->phases & 4);   // ... in its epilogue
   // both GroupGEMMs in one launch (only with the separate combine kernel and the LDS-resident schedule builder's
   // tile count, which bounds the per-workgroup tile counters)
   const bool one_launch = p->fuse_layers && (p->phases & 2) && (p->phases & 4) && !fused && !large;
@@ -488,6 +491,12 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   b.queue_len = ws.status + 32;
   b.queue_base = ws.status + 40;
   b.queue_stride = 1;
+  if (in_epilogue) {
+    b.epilogue_combine = 1;
+    b.arrive = ws.arrive;
+    b.perm = ws.perm;
+    if (launch_zero_u32(ws.arrive, (size_t)s.T * p->n_tiles_n1, st) != hipSuccess) return MOE_ERR_HIP;
+  }
 
   if (one_launch) {
     FuseParams f;
@@ -506,7 +515,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
     if ((p->phases & 4) && launch_layer1(b, grid1, st) != hipSuccess) return MOE_ERR_HIP;
   }
   if (!mark(3)) return MOE_ERR_HIP;
-  if ((p->phases & 8) && !(fused && (p->phases & 4))) {
+  if ((p->phases & 8) && !(fused && (p->phases & 4)) && !in_epilogue) {
     CombineParams c;
     c.Y = ws.Y;
     c.inv_perm = ws.inv_perm;

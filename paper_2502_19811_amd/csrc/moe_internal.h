@@ -50,6 +50,7 @@ struct Workspace {
   ItemRec* items0;        // [max_tiles * n_tiles_n0] layer0 schedule
   ItemRec* items1;        // [(max_tiles + 24) * n_tiles_n1] layer1 schedule, one contiguous queue per XCD
   uint32_t* panel_done;   // [n_tiles_n1] finished M-tiles per column panel of layer1
+  uint32_t* arrive;       // [T * n_tiles_n1] epilogue reduction: rows of a token already written, per column panel
   uint32_t* tile_done;    // [max_tiles + 1] one-launch variant: layer0 items finished per M-tile; last: workgroups done
   uint16_t* h;            // [R,F] bf16 activation buffer
   uint16_t* Y;            // [R,H] bf16 layer1 shared tensor
@@ -111,6 +112,9 @@ struct GemmParams {
   const int32_t* n_tiles;   // device scalar: M-tiles in total
   int32_t n_mfma;           // workgroups doing GEMM tiles; the rest are data-movement workgroups
   int32_t fused_combine;    // 1: data-movement workgroups reduce finished panels inside this kernel
+  int32_t epilogue_combine; // 1: the layer1 epilogue reduces a token once its last row has arrived (arrive[], perm)
+  uint32_t* arrive;         // [T * H/256] rows of a token already written, per column panel
+  const int32_t* perm;      // [R] sorted row -> pair id
   int32_t batch_publish;    // 1: no data-movement workgroups: a GEMM workgroup publishes all its tiles at its end
   // combine
   const int32_t* inv_perm;
@@ -155,6 +159,7 @@ hipError_t launch_layer0(const GemmParams& p, int act, int grid, hipStream_t st)
 hipError_t launch_layer1(const GemmParams& p, int grid, hipStream_t st);
 hipError_t launch_fused_layers(const GemmParams& p0, const GemmParams& p1, const FuseParams& f, int act, int grid, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+hipError_t launch_zero_u32(uint32_t* ptr, size_t n, hipStream_t st);
 hipError_t launch_pack_weights(const void* B, void* out, int E, int K, int ldb, int n_tiles_n, int swiglu_F, hipStream_t st);
 hipError_t launch_arrival_producer(const void* staging, void* x, const ArrivalParams& a, int n_wg, hipStream_t st);
 hipError_t launch_tile_heights(const int32_t* kind, int32_t* height, int n, hipStream_t st);

@@ -133,7 +133,7 @@ def test_full_size_variants_give_the_same_bits():
     base = _run(cfg, inp, ids, w)
     for opts, packed in (({"layer1_order": 1, "n_dm": 16}, False), ({"layer1_order": 1, "n_dm": 0}, False),
                          ({"layer0_order": 1}, False), ({}, True), ({"tile_m": 128}, False),
-                         ({"fuse_layers": 1, "spin_limit": 1 << 18}, True)):
+                         ({"fuse_layers": 1, "spin_limit": 1 << 18}, True), ({"layer1_order": 2}, True)):
         print(f"  options {opts} packed {packed}", flush=True)
         run = _run(cfg, inp, ids, w, opts, packed)
         np.testing.assert_array_equal(run.out, base.out)

@@ -110,6 +110,29 @@ def test_one_launch_for_both_groupgemms_gives_the_same_bits(H, cfg):
             np.testing.assert_array_equal(again.out, base.out)
 
 
+@pytest.mark.parametrize("cfg", SMALL_CASES, ids=lambda c: c.name)
+def test_reduction_in_the_layer1_epilogue_gives_the_same_bits(H, cfg):
+    """layer1_order 2: the row that arrives last of a token's k reduces the token inside the layer1 epilogue.  Same
+    bits as the separate combine kernel for k = 1, 2, 3, 8 and 16, every tile height, few and many workgroups, and
+    together with the one-launch variant of the two GroupGEMMs."""
+    print(f"epilogue-combine case {cfg.name}", flush=True)
+    inp = wl.make_inputs(cfg, threads=4)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    for tile_m in (64, 128, 256):
+        sep = H.GpuLayer(cfg, inp, ids, w, {"tile_m": tile_m})
+        sep.forward(); base = sep.results(); sep.close()
+        for extra in ({}, {"n_cu": 8}, {"fuse_layers": 1, "spin_limit": 1 << 16}):
+            opts = dict(extra, tile_m=tile_m, layer1_order=2)
+            print(f"  {opts}", flush=True)
+            layer = H.GpuLayer(cfg, inp, ids, w, opts)
+            layer.out.fill_(7.0)                                  # every output row must be written by somebody
+            layer.forward(); run = layer.results()
+            assert run.status == 0
+            np.testing.assert_array_equal(run.out, base.out)
+            layer.forward(); again = layer.results(); layer.close()   # the arrival counters start over
+            np.testing.assert_array_equal(again.out, base.out)
+
+
 def test_router_matches_oracle(H):
     import paper_2502_19811_amd as moe
     for (T, E, k, seed) in [(128, 4, 2, 1), (513, 64, 8, 2), (100, 8, 8, 3), (77, 16, 1, 4), (64, 200, 6, 5)]:
