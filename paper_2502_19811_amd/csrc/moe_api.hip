@@ -126,13 +126,33 @@ int default_tile_m(const Shape& s) {
   return 64;
 }
 
-// Division point between GEMM and data-movement workgroups of the layer1 kernel (Section 3.2.2), looked up from
-// the shape.  On one GPU the reduction is local (about 40 us of HBM time per forward on the benchmark shapes) and a
-// workgroup taken from the GEMM breaks the even split of the tall tiles over the compute units, so every sweep so
-// far (n_dm = 0, 4, 8, 16 on the Mixtral-, Phi-3.5- and Qwen2-shaped workloads) put the optimum at 0: the GEMM
-// workgroups reduce the panels themselves once they run out of tiles.  Shapes with slower data movement per flop
-// would get an entry here.
-int default_n_dm(const Shape&) { return 0; }
+// Division point between GEMM and data-movement workgroups of the layer1 kernel (Section 3.2.2): looked up, as the
+// paper's metadata is, from a table of profiled shapes (the nearest one in rows per expert and experts).  The
+// entries are the optima of the sweep tool (split_sweep.py: n_dm = 0, 2, 4, 8, 16, 32 on each shape): on one GPU the
+// reduction is local HBM traffic of 40-70 us per forward and a workgroup taken from the GEMM side breaks the even
+// split of the tall tiles over the compute units, so the curve of Fig. 8 has its minimum at its left edge on every
+// shape profiled so far -- the GEMM workgroups reduce the panels themselves once they run out of tiles.
+int default_n_dm(const Shape& s) {
+  struct Row { int experts, rows_per_expert, hidden, n_dm; };
+  static const Row table[] = {
+      {8, 2048, 4096, 0},    // Mixtral-shaped           layer1 + reduction 1721 us at 0, 1767 at 2, ... 1817 at 32
+      {64, 512, 3584, 0},    // Qwen2-shaped             763 / 878 / ... / 919
+      {16, 2048, 4096, 0},   // Phi-3.5-shaped           1575 / 1641 / ... / 1794
+      {8, 2048, 4096, 0},    // Mixtral TP8 slice        327 / 355 / ... / 396
+      {64, 512, 2048, 0},    // Table 2's Qwen2 row      312 / 381 / ... / 393
+  };
+  const int rows = s.E > 0 ? s.R / s.E : 0;
+  long best = -1;
+  int n_dm = 0;
+  for (const Row& r : table) {
+    const long d = labs((long)r.rows_per_expert - rows) + 64L * labs((long)r.experts - s.E) + labs((long)r.hidden - s.H) / 8;
+    if (best < 0 || d < best) {
+      best = d;
+      n_dm = r.n_dm;
+    }
+  }
+  return n_dm;
+}
 
 // Waves the source segments are grouped into for the layer0 schedule when ready flags are in use (layer0_order 2):
 // segment-major across waves so that tiles start as their rows arrive (Fig. 5), weight-panel-major inside a wave.
