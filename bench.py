@@ -32,6 +32,9 @@ def main() -> int:
     ap.add_argument("--packed", type=int, default=1, choices=[0, 1],
                     help="1 (default): the weights are re-laid out once, before the timed steps, with moe_pack_weights; "
                          "the layer is then also timed on the plain weights (10 steps, reported as plain_weights)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one forward in a HIP graph and time its replays (for launch-bound sizes such as the "
+                         "tiny workload); the per-phase events are then not recorded")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
                     help="tokens the CPU oracle is timed (and the GPU output checked) on; 8192 is the whole default workload")
@@ -93,17 +96,30 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    moe.moe_plan_set_option(plan, "profile", 1)
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            moe.moe_layer_forward(plan, x, ids, w, W1, W2, cfg.act, out, ws, None, 0, torch.cuda.current_stream())
+        eager_step, step = step, graph.replay
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+    else:
+        moe.moe_plan_set_option(plan, "profile", 1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    per_forward_us = sorted(v * 1e3 for v in moe.moe_plan_forward_times(plan, 256))
-    n_dropped = moe.moe_plan_get_option(plan, "profile_dropped")
-    phase_ms, n_prof = moe.moe_plan_phase_times(plan)
-    moe.moe_plan_set_option(plan, "profile", 0)
+    if args.graph:
+        per_forward_us, n_dropped, phase_ms, n_prof = [], 0, [0.0] * 4, 0
+        step = eager_step
+    else:
+        per_forward_us = sorted(v * 1e3 for v in moe.moe_plan_forward_times(plan, 256))
+        n_dropped = moe.moe_plan_get_option(plan, "profile_dropped")
+        phase_ms, n_prof = moe.moe_plan_phase_times(plan)
+        moe.moe_plan_set_option(plan, "profile", 0)
     status = moe.moe_last_device_status(plan, ws)
     assert status == 0, f"device status {status}"
 
@@ -167,6 +183,7 @@ def main() -> int:
                    "tile_m": moe.moe_plan_get_option(plan, "tile_m"), "n_dm": moe.moe_plan_get_option(plan, "n_dm"),
                    "layer1_order": moe.moe_plan_get_option(plan, "layer1_order"),
                    "weights_packed": moe.moe_plan_get_option(plan, "weights_packed"),
+                   "hip_graph_replay": bool(args.graph),
                    "gather": "fused into layer0's operand loads (no separate phase, no materialised copy)",
                    "device": device_info(torch),
                    "flop_per_layer": cfg.flops, "input_generation_s": round(t_gen, 1)},

@@ -16,6 +16,9 @@
 //    cannot start before all of its tokens have arrived);
 //  * the tile schedules are built on the device (index_build.hip): one queue of 32-byte item records per XCD,
 //    taken with one atomic per tile, a tile ahead, and stolen from the other XCDs' queues at the end.
+#include <atomic>
+#include <mutex>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -1036,11 +1039,48 @@ __global__ __launch_bounds__(256, 1) void k_fused_layers(GemmParams p0, GemmPara
   }
 }
 
+// The kernels need more dynamic LDS than the default limit.  The attribute belongs to the function on one device; it is
+// set once per function and device (a bit per device, set after the call succeeded: two threads racing set it twice,
+// which is harmless) and never inside a launch that may be under stream capture.
+static hipError_t allow_large_lds(const void* kern, int lds_bytes) {
+  struct Entry { const void* kern; std::atomic<uint64_t> devices; };
+  static Entry entries[16];
+  static std::atomic<int> n_entries{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  const int n = n_entries.load(std::memory_order_acquire);
+  for (int i = 0; i < n; i++)
+    if (entries[i].kern == kern && (entries[i].devices.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e != hipSuccess) return e;
+  for (int i = 0; i < n; i++)
+    if (entries[i].kern == kern) {
+      entries[i].devices.fetch_or(bit, std::memory_order_release);
+      return hipSuccess;
+    }
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
+  const int m = n_entries.load(std::memory_order_acquire);
+  for (int i = 0; i < m; i++)
+    if (entries[i].kern == kern) {
+      entries[i].devices.fetch_or(bit, std::memory_order_release);
+      return hipSuccess;
+    }
+  if (m < 16) {
+    entries[m].kern = kern;
+    entries[m].devices.store(bit, std::memory_order_release);
+    n_entries.store(m + 1, std::memory_order_release);
+  }
+  return hipSuccess;   // table full: the attribute is simply set again next time
+}
+
 template <int MODE0, bool PK>
 static hipError_t launch_fused(const GemmParams& p0, const GemmParams& p1, const FuseParams& f, int grid, hipStream_t st) {
   constexpr int lds = kLdsBytes;
   auto kern = k_fused_layers<MODE0, PK>;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  hipError_t e = allow_large_lds((const void*)kern, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p0, p1, f);
   return hipGetLastError();
@@ -1056,10 +1096,7 @@ template <int MODE, bool PK>
 static hipError_t launch_gemm(const GemmParams& p, int grid, hipStream_t st) {
   constexpr int lds = kLdsBytes;
   auto kern = k_group_gemm<MODE, PK>;
-  // The kernel needs more dynamic LDS than the default limit.  The attribute belongs to the function on the current
-  // device, so it is set on every launch (a host-side table look-up, no device work): a cached "done" flag would be
-  // wrong on a second device and racy between threads.
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  hipError_t e = allow_large_lds((const void*)kern, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, p);
   return hipGetLastError();
