@@ -1,5 +1,6 @@
-// GroupGEMM kernels of layer0 (gathered rows of x times W1, activation fused) and layer1 (h times W2, with
-// data-movement workgroups reducing finished column panels), for gfx950.
+// GroupGEMM kernels of layer0 (gathered rows of x times W1, activation fused) and layer1 (h times W2), the top-k
+// reduction in its three places (a kernel of its own, data-movement workgroups inside the layer1 kernel, the layer1
+// epilogue), the one-launch variant of the two GroupGEMMs, and the plan-time weight packing, for gfx950.
 //
 // Design (paper Section 3.2.1 maps to CDNA4 like this):
 //  * one persistent workgroup per compute unit walks a device-built tile schedule; a workgroup is either a
@@ -10,8 +11,9 @@
 //    B through a ring of 4 stages of depth 32, A through a ring of 5 blocks of half the tile's rows by depth 64, so
 //    that a load of A fetches whole 128-byte lines (8 rows per instruction); rows of A are gathered through
 //    per-lane row offsets that stay in registers for the whole tile (the row-index caching of Section 4);
-//  * A is read from LDS with ds_read_b128 (K-contiguous rows, XOR-swizzled by row), B (stored K x N as the
-//    weights are) with ds_read_b64_tr_b16, which hands every lane the 4 K-consecutive values of its column;
+//  * A is read from LDS with ds_read_b128 (K-contiguous rows, XOR-swizzled by row); B either as the weights are
+//    stored (K x N) with ds_read_b64_tr_b16, which hands every lane the 4 K-consecutive values of its column, or, with
+//    packed weights (k_pack_weights: every stage already an LDS image in operand order), with one ds_read_b128;
 //  * a layer0 tile waits for the ready flag of the source segment of its last row (Section 2.2.1: a tile
 //    cannot start before all of its tokens have arrived);
 //  * the tile schedules are built on the device (index_build.hip): one queue of 32-byte item records per XCD,

@@ -268,11 +268,13 @@ __global__ __launch_bounds__(256) void k_index_scatter(IndexParams p) {
 // consecutive positions should differ in the column tile and keep the M-tile: the workgroups of one XCD then
 // work on few column tiles of many M-tiles and share weight panels in their L2.  Tall tiles come first and the
 // short tiles of the ragged ends last, so that the short ones fill the gaps at the end of the kernel.
-// Layer0, order 0: per tile height, experts in order; inside an expert groups of 8 column tiles, the expert's
-// M-tiles, the 8 column tiles.  Order 1: per tile height, M-tiles by the segment they wait for (Fig. 5: rows that
-// are local or arrive early first), all column tiles of an M-tile in a row.
-// Layer1: per tile height, the M-tiles are dealt to the XCDs in contiguous chunks and every XCD sweeps its chunk
-// column-panel-major, 4 panels at a time (Fig. 6).
+// The orders (k_index_schedule, for up to 2048 M-tiles; see there for the locality order):
+// Layer0, order 0: locality order (blocks of an expert's M-tiles per XCD, column tiles ascending inside a block).
+// Order 1: per tile height, M-tiles by the segment they wait for (Fig. 5: rows that are local or arrive early first),
+// all column tiles of an M-tile in a row.  Order 2: the locality order inside waves of source segments, the waves in
+// arrival order.  Layer1: the locality order, or (in-kernel panel reduction) per tile height the M-tiles are dealt to
+// the XCDs in contiguous chunks and every XCD sweeps its chunk column-panel-major, 4 panels at a time (Fig. 6).
+// The one-workgroup builder below (any number of M-tiles) knows simpler versions of orders 0 and 1.
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileCap = kScheduleTileCap;  // tiles whose table fits the LDS copies of the schedule builder
 

@@ -63,6 +63,30 @@ def test_schedules_list_every_tile_once_in_the_documented_order(opts):
     H.check_schedule(items1, q1, run.tiles, n1, panel_major=opts.get("layer1_order") == 1)
 
 
+def test_wave_order_with_many_segments_and_uneven_experts():
+    """64 source segments of unequal size grouped into 8 and 5 waves, experts of very different load: the queues keep
+    their invariants and the output its bits."""
+    import gpu_harness as H
+    cfg = wl.MoEConfig("waves64", T=3000, H=256, F=256, E=16, k=4, act=wl.ACT_SWIGLU, S=64, seed=302, skew_zipf=1.2,
+                       dirichlet_segments=True)
+    inp = wl.make_inputs(cfg, threads=4)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    base_layer = H.GpuLayer(cfg, inp, ids, w, {"tile_m": 128})
+    base_layer.forward(); base = base_layer.results(); base_layer.close()
+    a, b = H.error_metrics(base.out, orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, cfg.act))
+    assert a <= H.REL_TOL and b <= H.REL_TOL
+    for n_waves in (8, 5):
+        layer = H.GpuLayer(cfg, inp, ids, w, {"tile_m": 128, "layer0_order": 2, "layer0_waves": n_waves})
+        layer.forward(); run = layer.results()
+        assert run.status == 0
+        items0, q0 = layer.schedule(0)
+        items1, q1 = layer.schedule(1)
+        layer.close()
+        H.check_schedule(items0, q0, run.tiles, cfg.F // 128, waves=(n_waves, cfg.S))
+        H.check_schedule(items1, q1, run.tiles, cfg.H // 256)
+        np.testing.assert_array_equal(run.out, base.out)
+
+
 def test_segment_boundaries_do_not_change_the_result():
     H, cfg, inp, ids, w, layer = _setup()
     layer.forward(); base = layer.results(); layer.close()
