@@ -115,3 +115,48 @@ def test_empty_batch_plan():
     plan = _create(T=0, seg_offsets=[0] * 9)
     assert moe.moe_plan_workspace_bytes(plan) > 0
     moe.moe_plan_destroy(plan)
+
+
+def test_static_forward_and_packing_argument_checks_happen_on_the_host():
+    lib = moe.load_library()
+    buf = C.create_string_buffer(4096)
+    addr = (C.addressof(buf) + 255) & ~255           # aligned, non-NULL, never dereferenced
+    # a plan whose workspace exceeds the library's fixed 32 MiB is refused before anything touches the GPU
+    big = _create(T=8192, H=4096, F=14336, E=8, k=2, act=moe.MOE_ACT_SWIGLU, seg_offsets=[1024 * i for i in range(9)])
+    assert moe.moe_plan_workspace_bytes(big) > 32 << 20
+    assert lib.moe_layer_forward_static(big, addr, addr, addr, addr, addr, moe.MOE_ACT_SWIGLU, addr, None, 0, None) == -3
+    assert lib.moe_layer_forward_static(None, addr, addr, addr, addr, addr, moe.MOE_ACT_SWIGLU, addr, None, 0, None) == -1
+    # packing: both pointers of a pair or neither, aligned, not in place
+    assert lib.moe_pack_weights(big, addr, None, None, None, None) == -1       # source without destination
+    assert lib.moe_pack_weights(big, addr, None, addr, None, None) == -1       # in place
+    assert lib.moe_pack_weights(big, addr, None, addr + 2, None, None) == -1   # misaligned destination
+    assert lib.moe_pack_weights(None, addr, None, addr + 256, None, None) == -1
+    assert lib.moe_pack_weights(big, None, None, None, None, None) == 0        # nothing to do is not an error
+    moe.moe_plan_destroy(big)
+
+
+def test_schedule_getter_sizes_and_argument_checks():
+    lib = moe.load_library()
+    plan = _create()                                  # T=128, H=256, F=512, GELU: 2 layer0 and 1 layer1 column tiles
+    mt = moe.moe_plan_max_tiles(plan)
+    assert moe.moe_plan_schedule_capacity(plan, 0) == mt * 2
+    assert moe.moe_plan_schedule_capacity(plan, 1) == (mt + 24) * 1
+    assert moe.moe_plan_schedule_capacity(plan, 2) == 0
+    q = (C.c_int32 * 24)()
+    assert lib.moe_get_schedule(plan, None, 0, None, q, None) == -1           # no workspace
+    assert lib.moe_get_schedule(plan, C.addressof(q), 3, None, q, None) == -1  # no such layer
+    moe.moe_plan_destroy(plan)
+
+
+def test_layer0_waves_come_from_the_table_unless_set():
+    plan = _create()
+    assert moe.moe_plan_get_option(plan, "layer0_order") == -1                # chosen per forward
+    assert moe.moe_plan_get_option(plan, "layer0_waves") == 4                 # 8 segments: the table's entry
+    moe.moe_plan_set_option(plan, "expected_ingest_gbps", 25)
+    assert moe.moe_plan_get_option(plan, "layer0_waves") == 4
+    moe.moe_plan_set_option(plan, "layer0_waves", 7)
+    assert moe.moe_plan_get_option(plan, "layer0_waves") == 7
+    moe.moe_plan_destroy(plan)
+    few = _create(S=2, seg_offsets=[0, 64, 128])
+    assert moe.moe_plan_get_option(few, "layer0_waves") == 2                  # never more waves than segments
+    moe.moe_plan_destroy(few)
