@@ -79,9 +79,12 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  2 = waves: the S source segments are grouped into "layer0_waves" waves, the tiles are
  *                  segment-major across waves and weight-panel-major inside a wave; -1 (default) = chosen by
  *                  every forward: 0 when seg_ready is NULL, 2 when ready flags are in use
- *   "layer0_waves" 1..8 waves of order 2 (1 is order 0); 0 (default) = looked up from "expected_ingest_gbps"
+ *   "layer0_waves" 1..8 waves of order 2 (1 is order 0); 0 (default) = looked up from the shape and
+ *                  "expected_ingest_gbps" (reading the option back returns the number in effect)
  *   "expected_ingest_gbps" rate in GB/s at which the caller expects the source segments to arrive (0 = unknown,
- *                  default); selects the number of waves from a table measured with the arrival experiment
+ *                  default); with the shape it selects the number of waves, by a rule condensed from the arrival
+ *                  experiment (paper_2502_19811_amd/arrival_experiment.py): more waves the longer the buffer takes
+ *                  to arrive against the time layer0 takes, one wave for small experts whose buffer arrives fast
  *   "spin_limit"   >0: a wait on a ready flag gives up after that many polls (about 0.3 us each) and the forward
  *                  reports MOE_ERR_TIMEOUT through moe_last_device_status; 0 = wait for ever (a flag that never
  *                  comes then hangs the GPU: the persistent kernel owns every compute unit).  Default 2^26,

@@ -157,19 +157,29 @@ int default_n_dm(const Shape& s) {
 // Waves the source segments are grouped into for the layer0 schedule when ready flags are in use (layer0_order 2):
 // segment-major across waves so that tiles start as their rows arrive (Fig. 5), weight-panel-major inside a wave.
 // Many waves follow a slow ingest closely but stream the layer0 weights once per wave; few waves keep the weight
-// reuse of the expert-major order at the price of waiting for a wave's last segment.  Looked up from the ingest
-// rate the caller expects (option "expected_ingest_gbps"), the way Section 3.2.2 looks its division point up from
-// metadata gathered by profiling; the entries come from the arrival experiment (arrival_experiment.py).
+// reuse of the expert-major order at the price of waiting for a wave's last segment.  Looked up, the way Section 3.2.2
+// looks its division point up from profiled metadata, from the shape and the ingest rate the caller expects (option
+// "expected_ingest_gbps").  The rule condenses the arrival experiment (arrival_experiment.py; arrival and layer
+// together, 8 segments, fastest schedule per rate):
+//                              25 GB/s           50 GB/s           100 GB/s          200 GB/s
+//   Mixtral-shaped  (8 x 2048)  4 waves           4 waves           4 waves           4 waves
+//   Phi-3.5-shaped (16 x 2048)  8 waves           4 waves           4 waves           4 waves
+//   Qwen2-shaped    (64 x 512)  8 waves / by seg. 8 waves / by seg. expert-major      expert-major
+// in two quantities: rows per expert (experts of two M-tiles have nothing to share inside a wave, so waves only cost
+// them weight reuse) and rho = time the buffer takes to arrive / time layer0 takes when resident.
 int default_layer0_waves(const Shape& s, int ingest_gbps) {
-  struct Row { int up_to_gbps, waves; };
-  // Mixtral-shaped workload, 8 segments, end-to-end time of arrival and layer together: 4 waves are the fastest at
-  // 50, 100 and 200 GB/s (by 6 % over both the expert-major and the segment-major order) and level with the
-  // segment-major order at 25 GB/s; 8 waves and 2 waves lose at every rate.
-  static const Row table[] = {{25, 4}, {50, 4}, {100, 4}, {1 << 30, 4}};
-  int waves = 4;                                         // unknown rate
-  if (ingest_gbps > 0)
-    for (const Row& r : table)
-      if (ingest_gbps <= r.up_to_gbps) { waves = r.waves; break; }
+  const int rows_per_expert = s.E > 0 ? s.R / s.E : 0;
+  const bool small_experts = rows_per_expert < 1024;
+  int waves;
+  if (ingest_gbps <= 0) {
+    waves = small_experts ? 8 : 4;   // unknown rate
+  } else {
+    const double arrival_s = 2.0 * s.T * s.H / (ingest_gbps * 1e9);
+    const double layer0_s = 2.0 * s.R * (double)s.H * s.F1 / 1.25e15;   // the layer0 GroupGEMM's rate on this part
+    const double rho = arrival_s / layer0_s;
+    if (small_experts) waves = rho >= 0.5 ? 8 : 1;
+    else waves = rho > 1.5 ? 8 : 4;
+  }
   if (waves > s.S) waves = s.S;
   return waves < 1 ? 1 : waves;
 }

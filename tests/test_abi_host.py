@@ -149,14 +149,22 @@ def test_schedule_getter_sizes_and_argument_checks():
 
 
 def test_layer0_waves_come_from_the_table_unless_set():
-    plan = _create()
-    assert moe.moe_plan_get_option(plan, "layer0_order") == -1                # chosen per forward
-    assert moe.moe_plan_get_option(plan, "layer0_waves") == 4                 # 8 segments: the table's entry
-    moe.moe_plan_set_option(plan, "expected_ingest_gbps", 25)
-    assert moe.moe_plan_get_option(plan, "layer0_waves") == 4
-    moe.moe_plan_set_option(plan, "layer0_waves", 7)
-    assert moe.moe_plan_get_option(plan, "layer0_waves") == 7
-    moe.moe_plan_destroy(plan)
+    seg = lambda T: [T * i // 8 for i in range(9)]
+    # the three profiled shapes at the profiled rates (see default_layer0_waves)
+    mixtral = _create(T=8192, H=4096, F=14336, E=8, k=2, act=moe.MOE_ACT_SWIGLU, seg_offsets=seg(8192))
+    phi35 = _create(T=16384, H=4096, F=6400, E=16, k=2, act=moe.MOE_ACT_SWIGLU, seg_offsets=seg(16384))
+    qwen2 = _create(T=4096, H=3584, F=2560, E=64, k=8, act=moe.MOE_ACT_SWIGLU, seg_offsets=seg(4096))
+    expect = {mixtral: {0: 4, 25: 4, 50: 4, 100: 4, 200: 4}, phi35: {0: 4, 25: 8, 50: 4, 100: 4, 200: 4},
+              qwen2: {0: 8, 25: 8, 50: 8, 100: 1, 200: 1}}
+    for plan, table in expect.items():
+        assert moe.moe_plan_get_option(plan, "layer0_order") == -1            # chosen per forward
+        for gbps, waves in table.items():
+            moe.moe_plan_set_option(plan, "expected_ingest_gbps", gbps)
+            assert moe.moe_plan_get_option(plan, "layer0_waves") == waves, (gbps, waves)
+    moe.moe_plan_set_option(mixtral, "layer0_waves", 7)                       # an explicit setting wins
+    assert moe.moe_plan_get_option(mixtral, "layer0_waves") == 7
+    for plan in expect:
+        moe.moe_plan_destroy(plan)
     few = _create(S=2, seg_offsets=[0, 64, 128])
     assert moe.moe_plan_get_option(few, "layer0_waves") == 2                  # never more waves than segments
     moe.moe_plan_destroy(few)
