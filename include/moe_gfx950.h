@@ -74,6 +74,13 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  against them): a tile writes its rows of Y, announces each on a counter per token and column
  *                  panel, and the row that arrives last of a token's k reduces that token.  All three give the
  *                  same bits
+ *   "n_prefetch"   0, 8, ... 64 (a multiple of 8): that many of the workgroups of each GroupGEMM launch compute no
+ *                  tiles but run ahead of the others of their XCD and read the packed weight panels of the items
+ *                  about to be handed out, "prefetch_behind" (default 16) items before to "prefetch_ahead"
+ *                  (default 16) items after the head of the XCD's queue (Section 3.2.1's specialised workgroups
+ *                  with local data movement to do; Section 3.2.2's division point).  Only with packed weights and
+ *                  full launches; same bits.  -1 (default) = looked up from the shape: 0 on every shape measured
+ *                  (there the workgroups cost their compute units and hide nothing)
  *   "layer0_order" order of the layer0 tiles: 0 = expert-major (weight reuse first); 1 = source-segment-major (Fig. 5:
  *                  M-tiles sorted by the segment they wait for, all column tiles of an M-tile in a row);
  *                  2 = waves: the S source segments are grouped into "layer0_waves" waves, the tiles are

@@ -4,7 +4,8 @@
 //
 // Design (paper Section 3.2.1 maps to CDNA4 like this):
 //  * one persistent workgroup per compute unit walks a device-built tile schedule; a workgroup is either a
-//    GEMM workgroup or a data-movement workgroup, chosen by its index (the division point of Section 3.2.2);
+//    GEMM workgroup or a data-movement workgroup, chosen by its index (the division point of Section 3.2.2); the
+//    data movement there is to do on one GPU: reducing finished column panels of layer1, prefetching weight panels;
 //  * a GEMM workgroup is 4 wavefronts, one per SIMD; a tile is BM x 256 outputs with BM = 256, 128 or 64, and
 //    accumulates in fp32 with v_mfma_f32_32x32x16_bf16;
 //  * operands go global -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no registers in between):
@@ -296,6 +297,63 @@ __device__ __forceinline__ int steal(const GemmParams& p, int xcd) {
   }
   return -1;
 }
+// Data-movement workgroup that runs ahead of the GEMM workgroups of its XCD (the specialisation of Section 3.2.1 put
+// to local use): it follows the head of the XCD's queue and reads one word of every 128-byte line of the packed
+// weight panel of the items about to be handed out, so that the panel is on its way from HBM into the Infinity Cache
+// (and this XCD's L2) before a GEMM workgroup's three K steps of lead have to cover the miss.  Pays where a weight
+// panel serves few M-tiles (many small experts): there the GEMM workgroups wait for HBM, not for the matrix cores.
+// `part` of `n_parts`: the workgroups sharing an XCD split every panel between them.  The loop ends when the queue is
+// handed out, or when its head has not moved for about a second (the GEMM side waiting for a ready flag): a
+// workgroup that stops prefetching costs time, never correctness.
+constexpr int kPrefetchUnroll = 16;
+__device__ __forceinline__ void prefetch_loop(const GemmParams& p, int xcd, int part, int n_parts) {
+  const int len = p.queue_len[xcd];
+  const int base = queue_pos(p, xcd, 0);
+  const uint64_t panel_bytes = (uint64_t)(p.K / BK) * B_STAGE;
+  const int lines = (int)(panel_bytes / 128);
+  const int tid = threadIdx.x;
+  int i = 0, last_expert = -1, last_n = -1;
+  uint32_t idle = 0, sink = 0;
+  while (i < len) {
+    const int head = uniform(__hip_atomic_load(&p.queue_heads[xcd], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (head >= len) break;   // everything handed out: nothing left to be ahead of
+    // items handed out a while ago are being streamed by their workgroups already
+    if (i < head - p.prefetch_behind) i = head - p.prefetch_behind;
+    if (i >= head + p.prefetch_ahead) {
+      if (++idle > (1u << 20)) break;
+      __builtin_amdgcn_s_sleep(32);
+      continue;
+    }
+    idle = 0;
+    const int expert = uniform(p.items[base + i * p.queue_stride].expert);
+    const int n_tile = uniform(p.items[base + i * p.queue_stride].n_tile);
+    i++;
+    if (expert == last_expert && n_tile == last_n) continue;   // the M-tiles of a block share the panel
+    last_expert = expert;
+    last_n = n_tile;
+    const char* src = p.B + ((uint64_t)expert * p.n_tiles_n + n_tile) * panel_bytes;
+    for (int l0 = part * 256 * kPrefetchUnroll; l0 < lines; l0 += n_parts * 256 * kPrefetchUnroll) {
+      uint32_t v[kPrefetchUnroll];
+#pragma unroll
+      for (int u = 0; u < kPrefetchUnroll; u++) {
+        const int l = l0 + u * 256 + tid;
+        v[u] = l < lines ? *(const uint32_t*)(src + (size_t)l * 128) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < kPrefetchUnroll; u++) sink ^= v[u];
+    }
+  }
+  if (p.K < 0) p.status[63] = (int32_t)sink;   // never true: keeps the loads
+}
+// The last n_prefetch workgroups of a launch take the prefetch role (multiples of 8: workgroup b runs on XCD b % 8,
+// so any 8 consecutive workgroups cover the 8 XCDs).
+__device__ __forceinline__ bool prefetch_role(const GemmParams& p) {
+  const int first = (int)gridDim.x - p.n_prefetch;
+  if (p.n_prefetch <= 0 || (int)blockIdx.x < first) return false;
+  prefetch_loop(p, blockIdx.x & (kXcds - 1), ((int)blockIdx.x - first) >> 3, p.n_prefetch >> 3);
+  return true;
+}
+
 __device__ __forceinline__ void block_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // Publishes one finished M-tile of column panel `panel` to the data-movement side: every wavefront makes its stores
@@ -848,6 +906,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   if (MODE == MODE_L1) {
     for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
   }
+  if (PK && prefetch_role(p)) return;
   if (MODE == MODE_L1 && (int)blockIdx.x >= p.n_mfma) {
     if (p.fused_combine) combine_loop(p, &lds_slot[1], false);
     return;

@@ -23,6 +23,8 @@ struct moe_plan {
   // options
   int32_t tile_m;
   int32_t n_dm;          // -1: table lookup
+  int32_t n_prefetch;    // -1: table lookup; workgroups of each GroupGEMM launch that prefetch packed weight panels
+  int32_t prefetch_ahead, prefetch_behind;   // items around the head of an XCD's queue they work on
   int32_t layer0_order;          // -1: chosen per forward (resident input: 0; ready flags in use: 2)
   int32_t layer0_waves;          // 0: from the table below
   int32_t expected_ingest_gbps;  // 0: unknown
@@ -154,6 +156,16 @@ int default_n_dm(const Shape& s) {
   return n_dm;
 }
 
+// Division point between GEMM workgroups and workgroups that prefetch weight panels ahead of them, per GroupGEMM
+// launch (Section 3.2.2 again: a number looked up from the shape).  Swept with bench.py (n_prefetch = 0, 8, 16, 24)
+// on the two shapes with 64 small experts, where a weight panel serves two M-tiles and the weight stream is 2 TB/s:
+// 683 / 703 / 720 / 743 us per forward on Table 2's Qwen2 row, 1859 / 1891 / 1925 / 1990 on the Qwen2-shaped workload.
+// The minimum is at 0 there, and shapes with larger experts have less to gain, so the look-up returns 0 throughout.
+int default_n_prefetch(const Shape& s) {
+  (void)s;
+  return 0;
+}
+
 // Waves the source segments are grouped into for the layer0 schedule when ready flags are in use (layer0_order 2):
 // segment-major across waves so that tiles start as their rows arrive (Fig. 5), weight-panel-major inside a wave.
 // Many waves follow a slow ingest closely but stream the layer0 weights once per wave; few waves keep the weight
@@ -214,6 +226,9 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
   memcpy(p->seg_offsets, seg_offsets, sizeof(int32_t) * (sh.S + 1));
   p->tile_m = default_tile_m(p->s);
   p->n_dm = -1;
+  p->n_prefetch = -1;
+  p->prefetch_ahead = 16;
+  p->prefetch_behind = 16;
   p->layer0_order = -1;
   p->layer1_order = 0;   // measured faster on every workload so far: see the sweep tool and default_n_dm
   p->serial = 0x2545F491;   // arbitrary start: an uninitialised workspace word is unlikely to match it
@@ -246,6 +261,16 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
   if (!strcmp(key, "n_dm")) {
     if (v < -1 || v > 240) return MOE_ERR_INVALID_ARG;
     p->n_dm = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "n_prefetch")) {
+    if (v < -1 || v > 64 || (v > 0 && v % 8 != 0)) return MOE_ERR_INVALID_ARG;
+    p->n_prefetch = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "prefetch_ahead") || !strcmp(key, "prefetch_behind")) {
+    if (v < 0 || v > 4096) return MOE_ERR_INVALID_ARG;
+    (key[9] == 'a' ? p->prefetch_ahead : p->prefetch_behind) = (int32_t)v;
     return MOE_OK;
   }
   if (!strcmp(key, "layer0_order")) {
@@ -338,6 +363,9 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   if (!p || !key || !v) return MOE_ERR_INVALID_ARG;
   if (!strcmp(key, "tile_m")) *v = p->tile_m;
   else if (!strcmp(key, "n_dm")) *v = p->n_dm >= 0 ? p->n_dm : default_n_dm(p->s);
+  else if (!strcmp(key, "n_prefetch")) *v = p->n_prefetch >= 0 ? p->n_prefetch : default_n_prefetch(p->s);
+  else if (!strcmp(key, "prefetch_ahead")) *v = p->prefetch_ahead;
+  else if (!strcmp(key, "prefetch_behind")) *v = p->prefetch_behind;
   else if (!strcmp(key, "layer0_order")) *v = p->layer0_order;
   else if (!strcmp(key, "layer0_waves")) *v = p->layer0_waves > 0 ? p->layer0_waves : default_layer0_waves(p->s, p->expected_ingest_gbps);
   else if (!strcmp(key, "expected_ingest_gbps")) *v = p->expected_ingest_gbps;
@@ -480,6 +508,14 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   const int64_t max_items0 = (int64_t)p->max_tiles * p->n_tiles_n0;
   const int grid0 = max_items0 < p->n_cu ? (max_items0 < 8 ? 8 : (int)max_items0) : p->n_cu;
   a.n_mfma = grid0;
+  // prefetching workgroups: only with packed weights, a full launch and the separate kernels
+  int n_prefetch = p->n_prefetch >= 0 ? p->n_prefetch : default_n_prefetch(s);
+  if (!p->weights_packed || fused || one_launch) n_prefetch = 0;
+  if (grid0 == p->n_cu && n_prefetch + 8 <= grid0) {
+    a.n_prefetch = n_prefetch;
+    a.prefetch_ahead = p->prefetch_ahead;
+    a.prefetch_behind = p->prefetch_behind;
+  }
   a.queue_heads = ws.status + 8;
   a.queue_len = ws.status + 24;
   if (order0 != 1 && !large) {
@@ -511,6 +547,11 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   int grid1 = p->n_cu;
   if (!fused && max_items1 < grid1) grid1 = max_items1 < 8 ? 8 : (int)max_items1;
   b.n_mfma = grid1 - n_dm;
+  if (grid1 == p->n_cu && n_prefetch + 8 <= grid1) {
+    b.n_prefetch = n_prefetch;
+    b.prefetch_ahead = p->prefetch_ahead;
+    b.prefetch_behind = p->prefetch_behind;
+  }
   b.fused_combine = fused ? 1 : 0;
   b.batch_publish = (fused && n_dm == 0 && s.H / kTileN <= 128) ? 1 : 0;
   b.inv_perm = ws.inv_perm;

@@ -133,11 +133,30 @@ def test_full_size_variants_give_the_same_bits():
     base = _run(cfg, inp, ids, w)
     for opts, packed in (({"layer1_order": 1, "n_dm": 16}, False), ({"layer1_order": 1, "n_dm": 0}, False),
                          ({"layer0_order": 1}, False), ({}, True), ({"tile_m": 128}, False),
-                         ({"fuse_layers": 1, "spin_limit": 1 << 18}, True), ({"layer1_order": 2}, True)):
+                         ({"fuse_layers": 1, "spin_limit": 1 << 18}, True), ({"layer1_order": 2}, True),
+                         ({"n_prefetch": 8}, True)):
         print(f"  options {opts} packed {packed}", flush=True)
         run = _run(cfg, inp, ids, w, opts, packed)
         np.testing.assert_array_equal(run.out, base.out)
         np.testing.assert_array_equal(run.perm, base.perm)
+
+
+def test_prefetching_workgroups_leave_the_output_unchanged():
+    """Table 2's Qwen2 row (64 small experts, the shape the weight prefetch is for): with 8, 16 and 32 of the 256
+    workgroups of each GroupGEMM launch prefetching weight panels instead of computing tiles, near and far ahead of
+    the queue heads, and with the strided queues of the source-segment order, the output is the default run's bit
+    for bit."""
+    cfg = wl.CONFIGS["qwen2_table2"]
+    print("prefetch qwen2_table2: generating inputs", flush=True)
+    inp = wl.make_inputs(cfg, threads=16)
+    ids, w = orc.route_topk(inp.logits, cfg.k)
+    base = _run(cfg, inp, ids, w, {}, True)
+    for opts in ({"n_prefetch": 8}, {"n_prefetch": 16, "prefetch_ahead": 4, "prefetch_behind": 0},
+                 {"n_prefetch": 32, "prefetch_ahead": 64, "prefetch_behind": 32}, {"n_prefetch": 8, "layer0_order": 1},
+                 {"n_prefetch": 16, "n_cu": 64}, {"n_prefetch": 8, "layer1_order": 2}):
+        print(f"  options {opts}", flush=True)
+        run = _run(cfg, inp, ids, w, opts, True)
+        np.testing.assert_array_equal(run.out, base.out)
 
 
 def test_skewed_output_does_not_depend_on_tiling_or_schedule():
