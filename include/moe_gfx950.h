@@ -74,6 +74,10 @@ int moe_plan_destroy(moe_plan_t *plan);
  *                  against them): a tile writes its rows of Y, announces each on a counter per token and column
  *                  panel, and the row that arrives last of a token's k reduces that token.  All three give the
  *                  same bits
+ *   "deep_short_tiles" 1 (default): the 64-row tiles of the ragged expert ends keep five K steps of operands in
+ *                  flight instead of three (six LDS stages; their A blocks are small enough).  A K step of such a tile
+ *                  is 8 MFMAs per wavefront, so with three steps of lead it spends half its time waiting for its
+ *                  operands.  Same bits; 0 is kept for comparison
  *   "n_prefetch"   0, 8, ... 64 (a multiple of 8): that many of the workgroups of each GroupGEMM launch compute no
  *                  tiles but run ahead of the others of their XCD and read the packed weight panels of the items
  *                  about to be handed out, "prefetch_behind" (default 16) items before to "prefetch_ahead"
@@ -252,13 +256,17 @@ int moe_plan_forward_times(moe_plan_t *plan, float *ms, int32_t capacity, int32_
  * moe_probe_copy: plain device copy of bytes (multiple of 16, both pointers 16-byte aligned) from src to dst;
  *   gbytes_per_s: host [1], bytes read plus bytes written per second.
  * moe_probe_mix: the same MFMA loop on random data with the data movement of a GroupGEMM K step around it, to price
- *   each kind of traffic at the board's power limit: mode is a bit mask -- 1: 8 ds_read_b128 per 16 MFMAs refresh the
- *   operand fragments from LDS; 2: 4 global->LDS loads of 1 KiB per 16 MFMAs from an L2-resident region; 4: a
- *   workgroup barrier per 16 MFMAs; 8 (needs 2): one load in four streams from HBM instead.  The loop runs twice
+ *   each kind of traffic at the board's power limit: mode is a bit mask -- 1: 8 ds_read_b128 per 16 MFMAs fetch the
+ *   operand fragments of the next 16 from LDS into a second register set; 2: 4 global->LDS loads of 1 KiB per 16
+ *   MFMAs from an L2-resident region; 4: a workgroup barrier per 32 MFMAs (a K step); 8 (needs 2): one load in four
+ *   streams from HBM instead.  The loop runs twice
  *   (warm-up, then timed), iters x 16 MFMAs per wavefront each.  scratch: dev, 16-byte aligned, at least 4 MiB, with
  *   bit 8 at least 4 MiB x (compute units + 1); its contents are read as operands and partly overwritten.
- *   tflops: host [1]. */
-int moe_probe_mix(int32_t mode, int32_t iters, void *scratch, size_t scratch_bytes, float *tflops, void *hip_stream);
+ *   tflops: host [1].  core_ghz: host [1] or NULL: the core clock inside the loop (cycle counter over the 100 MHz
+ *   device clock, mean over the workgroups), which tells a loop that runs slower because the board clocks lower from
+ *   one whose matrix cores wait: busy share = tflops / (compute units x 4 x core_ghz x 1024 flop per cycle). */
+int moe_probe_mix(int32_t mode, int32_t iters, void *scratch, size_t scratch_bytes, float *tflops, float *core_ghz,
+                  void *hip_stream);
 int moe_probe_mfma(int32_t random_data, int32_t iters, void *scratch, size_t scratch_bytes, float *tflops,
                    void *hip_stream);
 int moe_probe_copy(void *dst, const void *src, size_t bytes, float *gbytes_per_s, void *hip_stream);

@@ -37,7 +37,9 @@ class MoEShape(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), _LIB_NAME)
+    """The in-tree library; MOE_GFX950_LIB names another build of the same sources (the measurement tools use it for
+    builds with extra instrumentation)."""
+    return os.environ.get("MOE_GFX950_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), _LIB_NAME)
 
 
 def load_library():
@@ -88,7 +90,7 @@ def load_library():
     lib.moe_plan_forward_times.restype = C.c_int
     lib.moe_probe_mfma.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, C.POINTER(C.c_float), vp]
     lib.moe_probe_mfma.restype = C.c_int
-    lib.moe_probe_mix.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, C.POINTER(C.c_float), vp]
+    lib.moe_probe_mix.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
     lib.moe_probe_mix.restype = C.c_int
     lib.moe_probe_copy.argtypes = [vp, vp, C.c_size_t, C.POINTER(C.c_float), vp]
     lib.moe_probe_copy.restype = C.c_int
@@ -246,13 +248,15 @@ def moe_probe_mfma(random_data: bool, iters: int, scratch, stream=None) -> float
     return float(out.value)
 
 
-def moe_probe_mix(mode: int, iters: int, scratch, stream=None) -> float:
+def moe_probe_mix(mode: int, iters: int, scratch, stream=None, with_clock: bool = False):
     """TFLOP/s of the MFMA loop with GroupGEMM-like data movement around it (mode bits: 1 LDS reads, 2 global->LDS
-    loads, 4 barrier, 8 a quarter of the loads from HBM); scratch: a device tensor, see the header for its size."""
-    out = C.c_float()
+    loads, 4 barrier, 8 a quarter of the loads from HBM); scratch: a device tensor, see the header for its size.
+    with_clock: returns (TFLOP/s, core clock in GHz inside the loop)."""
+    out, ghz = C.c_float(), C.c_float()
     _check(load_library().moe_probe_mix(mode, iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
-                                        C.byref(out), _stream(stream)), "moe_probe_mix")
-    return float(out.value)
+                                        C.byref(out), C.byref(ghz) if with_clock else None, _stream(stream)),
+           "moe_probe_mix")
+    return (float(out.value), float(ghz.value)) if with_clock else float(out.value)
 
 
 def moe_probe_copy(dst, src, stream=None) -> float:

@@ -12,13 +12,14 @@ LIB_PATH = os.path.join(PKG_DIR, "libmoe_gfx950.so")
 SOURCES = ["moe_api.hip", "index_build.hip", "grouped_gemm.hip", "probes.hip"]
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH) -> str:
+    """Compiles the library.  extra_flags / out_path: builds with extra instrumentation go elsewhere than in-tree."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
            "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-o", out_path] + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -28,7 +29,7 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

@@ -356,6 +356,42 @@ __device__ __forceinline__ bool prefetch_role(const GemmParams& p) {
 
 __device__ __forceinline__ void block_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+#ifdef MOE_TILE_TRACE
+// Measurement build only (tile_trace.py compiles the library with -DMOE_TILE_TRACE): every workgroup notes, per tile,
+// the time (100 MHz device clock) at which it started on it, had the operands of the first K step in LDS, finished
+// the main loop and finished the epilogue; and, in core clock cycles, how long the main loop took and how much of that
+// its first wavefront spent at the synchronisation point of each K step (waiting for its operand loads to land and
+// for the other wavefronts).
+constexpr int kTraceWgs = 256, kTraceTiles = 128, kTraceWords = 6;
+__device__ uint64_t g_trace_stamp[2][kTraceWgs][kTraceTiles][kTraceWords];
+__device__ int32_t g_trace_kind[2][kTraceWgs][kTraceTiles];
+__device__ int32_t g_trace_count[2][kTraceWgs];
+// (The count is kept in LDS, slot: a load from global memory here would make the compiler wait for everything in
+// flight, the successor's first operand loads included.)
+__device__ __forceinline__ void trace_tile(int layer, int kind, uint64_t t0, uint64_t t1, uint64_t t2, uint64_t t3,
+                                           uint64_t loop_cycles, uint64_t sync_cycles, volatile uint32_t* slot) {
+  if (threadIdx.x != 0 || blockIdx.x >= kTraceWgs) return;
+  const int n = (int)slot[layer];
+  if (n >= kTraceTiles) return;
+  slot[layer] = (uint32_t)(n + 1);
+  g_trace_stamp[layer][blockIdx.x][n][0] = t0;
+  g_trace_stamp[layer][blockIdx.x][n][1] = t1;
+  g_trace_stamp[layer][blockIdx.x][n][2] = t2;
+  g_trace_stamp[layer][blockIdx.x][n][3] = t3;
+  g_trace_stamp[layer][blockIdx.x][n][4] = loop_cycles;
+  g_trace_stamp[layer][blockIdx.x][n][5] = sync_cycles;
+  g_trace_kind[layer][blockIdx.x][n] = kind;
+  g_trace_count[layer][blockIdx.x] = n + 1;
+}
+#define MOE_TRACE_STAMP(var) var = wall_clock64()
+#define MOE_TRACE_CYCLES(var) var = clock64()
+#define MOE_TRACE_ADD_CYCLES(sum, since) sum += clock64() - since
+#else
+#define MOE_TRACE_STAMP(var)
+#define MOE_TRACE_CYCLES(var)
+#define MOE_TRACE_ADD_CYCLES(sum, since)
+#endif
+
 // Publishes one finished M-tile of column panel `panel` to the data-movement side: every wavefront makes its stores
 // visible device-wide, then one thread bumps the panel's counter.
 __device__ __forceinline__ void publish_panel(const GemmParams& p, int panel) {
@@ -384,18 +420,24 @@ struct LoadState {
   const char* Bb;
 };
 
-// LDS of a tile of BM rows.  A is kept in a ring of kABlocks blocks, a block being one half of the tile's rows by 64
+// LDS of a tile of BM rows.  B is kept in a ring of NSX stages of one K step, loaded NSX - 1 steps ahead; A in a ring
+// of NSX + 1 blocks in front of it, a block being one half of the tile's rows by 64
 // values of K (128 bytes per row: whole cache lines of the operand, 8 rows per load instruction; fetching the 64
 // bytes of one K step per row, 16 rows per instruction, is 1-2 % slower).  Block b = 2d + h holds rows [h*BM/2, (h+1)*BM/2) for
-// K steps 2d and 2d+1.  B is kept in a ring of NS stages of one K step behind it.
-constexpr int kABlocks = 5;
+// K steps 2d and 2d+1; a block per K step is loaded, NSX - 1 steps ahead like B.
+// NSX is 4 (three steps of lead) except for the 64-row tiles of the ragged expert ends, which get 6: a K step of
+// theirs is 8 MFMAs per wavefront, so three steps of lead are a third of a memory round trip and the tile would
+// spend half its time waiting for its operands; their small A blocks leave the LDS for two more B stages.
+constexpr int kDeepStages = 6;
 constexpr int a_block_bytes(int bm) { return bm * 64; }
-constexpr int b_ring_offset(int bm) { return kABlocks * a_block_bytes(bm); }
+constexpr int b_ring_offset(int bm, int nsx) { return (nsx + 1) * a_block_bytes(bm); }
 // The epilogue stages C in 32 KiB that are free at the end of a tile even when the successor's first loads are under
 // way (A blocks 0..2, B stages 0..2): A blocks 3 and 4 of a 256-row tile, the space behind the rings otherwise.
-constexpr int staging_offset(int bm) { return bm == 256 ? 3 * a_block_bytes(bm) : b_ring_offset(bm) + NS * B_STAGE; }
-constexpr int kLdsBytes = b_ring_offset(256) + NS * B_STAGE;   // 144 KiB; covers the smaller tiles' layouts too
-static_assert(staging_offset(128) + 32768 <= kLdsBytes && staging_offset(64) + 32768 <= kLdsBytes, "staging fits");
+constexpr int staging_offset(int bm, int nsx) { return bm == 256 ? 3 * a_block_bytes(bm) : b_ring_offset(bm, nsx) + nsx * B_STAGE; }
+constexpr int kLdsBytesShallow = b_ring_offset(256, NS) + NS * B_STAGE;   // 144 KiB; covers the smaller tiles' layouts with NSX = 4 too
+constexpr int kLdsBytes = staging_offset(64, kDeepStages) + 32768;         // 156 KiB: the 64-row tiles with 6 stages
+static_assert(staging_offset(128, NS) + 32768 <= kLdsBytesShallow && staging_offset(64, NS) + 32768 <= kLdsBytesShallow, "staging fits");
+static_assert(kLdsBytes >= kLdsBytesShallow && kLdsBytes <= 160 * 1024 - 2048, "LDS of a compute unit, less the kernels' static variables");
 
 // Rows of A the lane loads for a tile of the given height class: LA = 1, 2 or 4 loads per block and two blocks (row
 // halves) per tile; a load covers 8 rows, 8 lanes per row.  arow[h * LA + j]: row half h, load j.
@@ -413,17 +455,19 @@ __device__ __forceinline__ void load_arows(const GemmParams& p, Tile& t, int lan
   }
 }
 
-// Address set-up of a tile and its first loads: A blocks 0..2 and B stages 0..2, in the order A0 A1 B0 A2 B1 B2.
+// Address set-up of a tile and its first loads: A blocks and B stages 0 .. NSX-2, in the order A0 A1 B0 A2 B1 ...
+// A(NSX-2) B(NSX-3) B(NSX-2) (what K step 0 needs first, then a block and a stage per further step).
 // A: lane l of a load fetches the 16 bytes at position (l & 7) ^ ((row / 2) & 7) of its row's 128-byte line, so that
 // the line lands in LDS (linearly, 16 bytes per lane) with its chunks XOR-swizzled by row: the 16 rows one pass of
 // ds_read_b128 touches then fall on distinct banks.
-template <int WM, int MT, int NT, int MODE, bool PK>
+template <int WM, int MT, int NT, int MODE, bool PK, int NSX>
 __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t lds0, const Tile& t, LoadState& ls, int lane,
                                                 int w, bool issue) {
   constexpr int BM = WM * MT * 32;
   constexpr int A_BLOCK = a_block_bytes(BM);
-  constexpr int B_RING = b_ring_offset(BM);
+  constexpr int B_RING = b_ring_offset(BM, NSX);
   constexpr int LA = BM / 64, LB = 4;
+  constexpr int LEAD = NSX - 1;   // K steps the loads run ahead
 #pragma unroll
   for (int i = 0; i < 2 * LA; i++) {
     const int r = (w * LA + i % LA) * 8 + (lane >> 3);   // row inside the block
@@ -470,11 +514,14 @@ __device__ __forceinline__ void setup_and_issue(const GemmParams& p, uint32_t ld
     a_block(0);
     a_block(1);
     b_stage(0);
-    a_block(2);
-    b_stage(1);
-    b_stage(2);
+#pragma unroll
+    for (int st = 2; st < LEAD; st++) {
+      a_block(st);
+      b_stage(st - 1);
+    }
+    b_stage(LEAD - 1);
   }
-  ls.Bb += (NS - 1) * bstep;   // ls.Ab stays the row start: the K position of A comes from the block number
+  ls.Bb += LEAD * bstep;   // ls.Ab stays the row start: the K position of A comes from the block number
 }
 
 // Workgroup-wide: is the source segment of tile t there?  block = true waits for it (up to the spin limit).
@@ -505,7 +552,7 @@ __device__ __forceinline__ bool segment_ready(const GemmParams& p, const Tile& t
 // through LDS and the item record is requested.  A tile followed by one of the same height also starts the
 // successor's first operand stages during its own epilogue (next.pre = 1); otherwise only the rows of A the next
 // tile gathers are requested, after the epilogue.  next.idx = -1: no further tile.
-template <int WM, int MT, int NT, int MODE, bool PK>
+template <int WM, int MT, int NT, int MODE, bool PK, int NSX = NS>
 __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volatile int32_t* lds_slot, const Tile& cur,
                                          Tile& next, int xcd, const Queue& q, int& pending_panel,
                                          volatile int32_t* lds_panel_count_ptr, volatile uint32_t* lds_mask) {
@@ -513,12 +560,19 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   constexpr int BM = WM * MT * 32;
   static_assert(WN * NT * 32 == BN, "tile must be 256 columns wide");
   constexpr int A_BLOCK = a_block_bytes(BM);
-  constexpr int B_RING = b_ring_offset(BM);
+  constexpr int B_RING = b_ring_offset(BM, NSX);
+  constexpr int AB = NSX + 1;     // blocks of the A ring
+  constexpr int LEAD = NSX - 1;   // K steps the loads run ahead; odd, so that the steps without loads at the end start on an odd step
+  static_assert(LEAD % 2 == 1 && (BM != 256 || NSX == NS), "see staging_offset: the 256-row epilogue stages in A blocks 3 and 4");
   constexpr int LA = BM / 64;  // A loads per lane per K step (one block)
   constexpr int LB = 4;        // B loads per lane per K step (one stage)
   constexpr int LS = LA + LB;
   constexpr int FPB = BM / 64; // 32-row fragments per A block
 
+#ifdef MOE_TILE_TRACE
+  uint64_t tt0 = 0, tt1 = 0, tt2 = 0, tt3 = 0, tc_loop = 0, tc_sync = 0, tc_mark = 0;
+#endif
+  MOE_TRACE_STAMP(tt0);
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
   // The thread index is made opaque per tile: otherwise the lane-dependent address constants of all three tile
   // heights are hoisted out of the tile loop, kept live across it and spilled.
@@ -559,7 +613,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   if (MODE == MODE_L1 && p.handoff_fences) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   // address set-up and the first loads (A blocks 0..2, B stages 0..2)
   LoadState ls;
-  setup_and_issue<WM, MT, NT, MODE, PK>(p, lds0, cur, ls, lane, w, !cur.pre);
+  setup_and_issue<WM, MT, NT, MODE, PK, NSX>(p, lds0, cur, ls, lane, w, !cur.pre);
   const char* Ab = uniform(ls.Ab);
   const char* Bb = uniform(ls.Bb);
   const size_t bstep = PK ? (size_t)B_STAGE : (size_t)BK * p.ldb * 2;
@@ -570,13 +624,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int j = 0; j < NT; j++) acc[i][j] = (f32x16){0};
 
-  // Per K step and lane: LA loads of A (block kt+3: the other half of the rows than the block before, 64 values of K)
-  // and LB loads of B (stage kt+3).  The loads are issued one at a time between groups of MFMAs: a burst would fill
+  // Per K step and lane: LA loads of A (block kt+LEAD: the other half of the rows than the block before, 64 values of K)
+  // and LB loads of B (stage kt+LEAD).  The loads are issued one at a time between groups of MFMAs: a burst would fill
   // the vector-memory queue and stall the MFMAs queued behind it.
   using P0 = std::integral_constant<int, 0>;
   using P1 = std::integral_constant<int, 1>;
   // LDS offset of the A block that holds row half hh for K step `step`
-  auto a_slot = [&](int step, int hh) { return (uint32_t)((2 * (step >> 1) + hh) % kABlocks) * A_BLOCK; };
+  auto a_slot = [&](int step, int hh) { return (uint32_t)((2 * (step >> 1) + hh) % AB) * A_BLOCK; };
   // where fragment q (32 rows) of this wavefront sits: row half and offset inside the block
   auto frag_off = [&](const uint32_t (&blk)[2], int q) {
     const int f = wm * MT + q;   // WM == 2: f / FPB == wm for every q
@@ -617,27 +671,27 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     for (int i = PER; i < 12; i++)
       if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   };
-  // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+3
+  // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+LEAD
   auto half1 = [&](auto par, int kt, bool do_issue) {
     constexpr int PAR = decltype(par)::value;
     const uint32_t blk[2] = {a_slot(kt, 0), a_slot(kt, 1)};
-    const uint32_t b_off = (uint32_t)(kt % NS) * B_STAGE;
-    const int b = kt + 3;
+    const uint32_t b_off = (uint32_t)(kt % NSX) * B_STAGE;
+    const int b = kt + LEAD;
     const char* src = Ab + (b >> 1) * 128;
-    const uint32_t dst = lds0 + (uint32_t)(b % kABlocks) * A_BLOCK + w * LA * 1024;
+    const uint32_t dst = lds0 + (uint32_t)(b % AB) * A_BLOCK + w * LA * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
-      if (do_issue && q < LA) dma16(src, ls.aoff[(1 - PAR) * LA + q], dst + q * 1024);
+      if (do_issue && q < LA) dma16(src, ls.aoff[((PAR + LEAD) & 1) * LA + q], dst + q * 1024);
       group(0, 1, blk, b_off, PAR, 1, q);
     }
   };
-  // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+3
+  // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+LEAD
   auto half2 = [&](auto par, int kt, bool do_issue) {
     constexpr int PAR = decltype(par)::value;
     const uint32_t blk[2] = {a_slot(kt + 1, 0), a_slot(kt + 1, 1)};
-    const uint32_t b_off = (uint32_t)((kt + 1) % NS) * B_STAGE;
-    const uint32_t dst = lds0 + B_RING + (uint32_t)((kt + 3) % NS) * B_STAGE + w * LB * 1024;
+    const uint32_t b_off = (uint32_t)((kt + 1) % NSX) * B_STAGE;
+    const uint32_t dst = lds0 + B_RING + (uint32_t)((kt + LEAD) % NSX) * B_STAGE + w * LB * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);
@@ -661,10 +715,12 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     flag_v = __hip_atomic_load(&p.seg_ready[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 
   const int nk = p.K / BK;  // even and >= 4 (checked on the host)
-  // A blocks 0 and 1 and B stage 0 landed?  Everything issued after them (A block 2, B stages 1 and 2, and whatever
-  // the previous tile's epilogue stored) may still be outstanding; loads return in order.
-  wait_vmcnt<LA + 2 * LB>();
+  // A blocks 0 and 1 and B stage 0 landed?  Everything issued after them (A blocks 2 .. LEAD-1, B stages 1 .. LEAD-1, and
+  // whatever the previous tile's epilogue stored) may still be outstanding; loads return in order.
+  wait_vmcnt<(LEAD - 2) * LA + (LEAD - 1) * LB>();
   block_barrier();
+  MOE_TRACE_STAMP(tt1);
+  MOE_TRACE_CYCLES(tc_loop);
   {
     const uint32_t blk[2] = {a_slot(0, 0), a_slot(0, 1)};
 #pragma unroll
@@ -676,25 +732,46 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   int kt = 0;
   auto step = [&](auto par) {
     half1(par, kt, true);
-    // B stage kt+1 and the A blocks of step kt+1 have landed for this lane (younger: B stage kt+2 and A block kt+3);
-    // after the barrier they have for all, and all are done reading step kt.  The scheduler must not move MFMAs of the
+    // B stage kt+1 and the A blocks of step kt+1 (up to block kt+2) have landed for this lane; younger, in issue
+    // order: B stage kt+2, blocks and stages kt+3 .. kt+LEAD-1, A block kt+LEAD: LEAD-2 steps' worth of loads.
+    // After the barrier they have for all, and all are done reading step kt.  The scheduler must not move MFMAs of the
     // first half behind the barrier: they are what covers the latency of the half's LDS reads before the wait.
     __builtin_amdgcn_sched_barrier(0);
-    wait_vmcnt<LS>();
+    MOE_TRACE_CYCLES(tc_mark);
+    wait_vmcnt<(LEAD - 2) * LS>();
     block_barrier();
+    MOE_TRACE_ADD_CYCLES(tc_sync, tc_mark);
     __builtin_amdgcn_sched_barrier(0);
     half2(par, kt, true);
     Bb += bstep;
     kt++;
   };
-  const int kt_end = nk - (NS - 1);   // odd
+  const int kt_end = nk - LEAD;   // odd; at least 1 (the caller picks NSX so that nk > LEAD)
   while (kt + 2 <= kt_end) {
     step(P0{});
     step(P1{});
   }
   if (kt < kt_end) step(P0{});
 
-  // the last three steps (parities 1, 0, 1) issue nothing
+  // The last LEAD steps (parities 1, 0, ..., 1) issue nothing.  With r steps still to come after the current one, what
+  // is younger than the loads the step waits for is B stage kt+2 and the blocks and stages of the r-2 steps after it.
+  static_assert(LEAD == 3 || LEAD == 5, "the steps without loads are written out for these two");
+  if constexpr (LEAD == 5) {
+    half1(P1{}, kt, false);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<LB + 2 * LS>();
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    half2(P1{}, kt, false);
+    kt++;
+    half1(P0{}, kt, false);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<LB + LS>();
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    half2(P0{}, kt, false);
+    kt++;
+  }
   half1(P1{}, kt, false);
   wait_vmcnt<LB>();   // younger than the last A block: the last B stage
   block_barrier();
@@ -739,6 +816,10 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   }
   if (MODE != MODE_L1 && p.handoff_fences) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the previous tile's stores
   block_barrier();   // every wavefront is done reading the operand stages
+  MOE_TRACE_STAMP(tt2);
+#ifdef MOE_TILE_TRACE
+  tc_loop = clock64() - tc_loop;
+#endif
 
   if (next.idx >= 0) next.rec = make_uniform(raw_rec);
   // early start of the successor (see above): its gather rows are requested now, its first loads after the first
@@ -765,7 +846,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   constexpr int NST = 32 * PNC / 64;                                // 16-byte stores per lane and piece
   constexpr int NPIECE = MT * PH;
   static_assert(OUT_NT % PW == 0, "pieces tile the wavefront's columns");
-  const uint32_t cbase = lds0 + staging_offset(BM) + w * (2 * 32 * PRB);   // 2 buffers x 32 rows x 128 bytes per wavefront
+  const uint32_t cbase = lds0 + staging_offset(BM, NSX) + w * (2 * 32 * PRB);   // 2 buffers x 32 rows x 128 bytes per wavefront
   int lane_e = lane;   // opaque again: the epilogue's addresses are computed here, not before the main loop
   asm volatile("" : "+v"(lane_e));
   const int col_base = (MODE == MODE_L0_SWIGLU) ? col0 + wn * (NT * 16) : col0 + wn * (NT * 32);
@@ -829,7 +910,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       if (s == PH && do_pre) {   // the first 32-row block is out
         if (flags_on) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
         LoadState ls_next;
-        setup_and_issue<WM, MT, NT, MODE, PK>(p, lds0, next, ls_next, lane_e, w, true);
+        setup_and_issue<WM, MT, NT, MODE, PK, NSX>(p, lds0, next, ls_next, lane_e, w, true);
       }
     }
   }
@@ -848,8 +929,8 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // Nobody waits for anybody; the price is one device-wide release per tile (the rows must be visible before they are
   // announced) and one acquire.
   if (MODE == MODE_L1 && p.epilogue_combine) {
-    volatile int32_t* last_list = (volatile int32_t*)(smem + staging_offset(BM));   // the staging area is free again
-    int32_t* last_count = (int32_t*)(smem + staging_offset(BM) + 256 * 4);
+    volatile int32_t* last_list = (volatile int32_t*)(smem + staging_offset(BM, NSX));   // the staging area is free again
+    int32_t* last_count = (int32_t*)(smem + staging_offset(BM, NSX) + 256 * 4);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     __syncthreads();
     if (tid == 0) *last_count = 0;
@@ -894,15 +975,22 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   }
   // rows of A the next tile gathers (requested only now: held across the epilogue they push it into spilling)
   if (next.idx >= 0 && !do_pre) load_arows<MODE>(p, next, lane, w);
+#ifdef MOE_TILE_TRACE
+  MOE_TRACE_STAMP(tt3);
+  trace_tile(MODE == MODE_L1 ? 1 : 0, kKind + (cur.pre ? 4 : 0), tt0, tt1, tt2, tt3, tc_loop, tc_sync, lds_mask + 2);
+#endif
 }
 
 template <int MODE, bool PK>
 __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int32_t lds_slot[2];
-  __shared__ uint32_t lds_mask[2];
+  __shared__ uint32_t lds_mask[4];   // 0, 1: ready flags seen by the workgroup; 2, 3: tiles noted by a measurement build
   __shared__ int32_t lds_panel_count[kMaxPanels];   // layer1, batched publication: tiles finished per column panel
   const int tid = threadIdx.x;
+#ifdef MOE_TILE_TRACE
+  if (tid == 0) lds_mask[2] = lds_mask[3] = 0;
+#endif
   if (MODE == MODE_L1) {
     for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
   }
@@ -917,6 +1005,8 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   q.own_len = p.queue_len[xcd];
   q.own_base = queue_pos(p, xcd, 0);
   int pending_panel = -1;   // layer1: column panel of the last finished tile, not yet published
+  // 64-row tiles run with the deeper operand rings whenever the reduction is long enough to fill them
+  const bool deep64 = p.deep_short_tiles && p.K / BK > kDeepStages - 1;
 
   // first tile: found synchronously
   Tile cur, next;
@@ -946,6 +1036,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
     next.idx = -1;
     if (cur.rec.kind == 2) run_tile<2, 4, 4, MODE, PK>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
     else if (cur.rec.kind == 1) run_tile<2, 2, 4, MODE, PK>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
+    else if (deep64) run_tile<1, 2, 2, MODE, PK, kDeepStages>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
     else run_tile<1, 2, 2, MODE, PK>(p, smem, lds_slot, cur, next, xcd, q, pending_panel, lds_panel_count, lds_mask);
     cur = next;
   }
@@ -979,10 +1070,13 @@ template <int MODE0, bool PK>
 __global__ __launch_bounds__(256, 1) void k_fused_layers(GemmParams p0, GemmParams p1, FuseParams f) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int32_t lds_slot[2];
-  __shared__ uint32_t lds_mask[2];
+  __shared__ uint32_t lds_mask[4];   // 0, 1: ready flags seen by the workgroup; 2, 3: tiles noted by a measurement build
   __shared__ int32_t lds_panel_count[kMaxPanels];      // unused here; run_tile takes it
   __shared__ int32_t lds_tile_cnt[kScheduleTileCap];   // layer0 tiles this workgroup finished per M-tile, not yet published
   const int tid = threadIdx.x;
+#ifdef MOE_TILE_TRACE
+  if (tid == 0) lds_mask[2] = lds_mask[3] = 0;
+#endif
   for (int i = tid; i < kScheduleTileCap; i += 256) lds_tile_cnt[i] = 0;
   for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
   const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1139,7 +1233,7 @@ static hipError_t allow_large_lds(const void* kern, int lds_bytes) {
 
 template <int MODE0, bool PK>
 static hipError_t launch_fused(const GemmParams& p0, const GemmParams& p1, const FuseParams& f, int grid, hipStream_t st) {
-  constexpr int lds = kLdsBytes;
+  constexpr int lds = kLdsBytesShallow;   // (its per-M-tile counters take 8 KiB of LDS; every tile height runs with 4 stages)
   auto kern = k_fused_layers<MODE0, PK>;
   hipError_t e = allow_large_lds((const void*)kern, lds);
   if (e != hipSuccess) return e;
@@ -1270,3 +1364,23 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t st) {
 }
 
 }  // namespace moe
+
+#ifdef MOE_TILE_TRACE
+// Measurement build only.  reset != 0: forget the tiles noted so far.  Otherwise copies out, per layer (0, 1) and
+// workgroup (256), the number of tiles noted, and per tile (128 slots) the four time stamps, the two cycle counts and the height class
+// (0 / 1 / 2 for 64 / 128 / 256 rows, +4 when the tile's first loads were started by its predecessor).  Host pointers.
+extern "C" int moe_debug_tile_trace(int reset, uint64_t* stamps, int32_t* kinds, int32_t* counts) {
+  if (hipDeviceSynchronize() != hipSuccess) return MOE_ERR_HIP;
+  if (reset) {
+    static const int32_t zeros[2][moe::kTraceWgs] = {};
+    return hipMemcpyToSymbol(HIP_SYMBOL(moe::g_trace_count), zeros, sizeof(zeros)) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+  }
+  if (!stamps || !kinds || !counts) return MOE_ERR_INVALID_ARG;
+  if (hipMemcpyFromSymbol(stamps, HIP_SYMBOL(moe::g_trace_stamp), sizeof(uint64_t) * 2 * moe::kTraceWgs * moe::kTraceTiles * moe::kTraceWords) != hipSuccess ||
+      hipMemcpyFromSymbol(kinds, HIP_SYMBOL(moe::g_trace_kind), sizeof(int32_t) * 2 * moe::kTraceWgs * moe::kTraceTiles) != hipSuccess ||
+      hipMemcpyFromSymbol(counts, HIP_SYMBOL(moe::g_trace_count), sizeof(int32_t) * 2 * moe::kTraceWgs) != hipSuccess)
+    return MOE_ERR_HIP;
+  return MOE_OK;
+}
+#endif
+

@@ -23,6 +23,7 @@ struct moe_plan {
   // options
   int32_t tile_m;
   int32_t n_dm;          // -1: table lookup
+  int32_t deep_short_tiles;   // 1: 64-row tiles run with six operand stages instead of four
   int32_t n_prefetch;    // -1: table lookup; workgroups of each GroupGEMM launch that prefetch packed weight panels
   int32_t prefetch_ahead, prefetch_behind;   // items around the head of an XCD's queue they work on
   int32_t layer0_order;          // -1: chosen per forward (resident input: 0; ready flags in use: 2)
@@ -227,6 +228,7 @@ int moe_plan_create(moe_plan_t** plan, const moe_shape_t* shape, const int32_t* 
   p->tile_m = default_tile_m(p->s);
   p->n_dm = -1;
   p->n_prefetch = -1;
+  p->deep_short_tiles = 1;
   p->prefetch_ahead = 16;
   p->prefetch_behind = 16;
   p->layer0_order = -1;
@@ -261,6 +263,11 @@ int moe_plan_set_option(moe_plan_t* p, const char* key, int64_t v) {
   if (!strcmp(key, "n_dm")) {
     if (v < -1 || v > 240) return MOE_ERR_INVALID_ARG;
     p->n_dm = (int32_t)v;
+    return MOE_OK;
+  }
+  if (!strcmp(key, "deep_short_tiles")) {
+    if (v != 0 && v != 1) return MOE_ERR_INVALID_ARG;
+    p->deep_short_tiles = (int32_t)v;
     return MOE_OK;
   }
   if (!strcmp(key, "n_prefetch")) {
@@ -364,6 +371,7 @@ int moe_plan_get_option(const moe_plan_t* p, const char* key, int64_t* v) {
   if (!strcmp(key, "tile_m")) *v = p->tile_m;
   else if (!strcmp(key, "n_dm")) *v = p->n_dm >= 0 ? p->n_dm : default_n_dm(p->s);
   else if (!strcmp(key, "n_prefetch")) *v = p->n_prefetch >= 0 ? p->n_prefetch : default_n_prefetch(p->s);
+  else if (!strcmp(key, "deep_short_tiles")) *v = p->deep_short_tiles;
   else if (!strcmp(key, "prefetch_ahead")) *v = p->prefetch_ahead;
   else if (!strcmp(key, "prefetch_behind")) *v = p->prefetch_behind;
   else if (!strcmp(key, "layer0_order")) *v = p->layer0_order;
@@ -480,6 +488,7 @@ int forward_impl(moe_plan_t* p, const void* x, const int32_t* topk_ids, const fl
   g.k = s.k;
   g.H = s.H;
   g.handoff_fences = p->handoff_fences;
+  g.deep_short_tiles = p->deep_short_tiles;
 
   const bool fused = p->layer1_order == 1 && (p->phases & 8);   // top-k reduction inside the layer1 kernel
   const bool in_epilogue = p->layer1_order == 2 && (p->phases & 8) && (p->phases & 4);   // ... in its epilogue

@@ -88,6 +88,7 @@ struct GemmParams {
   int32_t n_tiles_n;        // column tiles of this layer (addressing of packed B)
   int32_t handoff_fences;   // measurement aid: per-tile agent-scope release (layer0) / acquire (layer1)
   int32_t no_pre;           // 1: a tile never starts its successor's loads early (the successor's rows may not be there)
+  int32_t deep_short_tiles; // 1: 64-row tiles keep five K steps of operands in flight instead of three
   int32_t n_prefetch;       // workgroups (the last of the launch, a multiple of 8) that prefetch packed weight panels
   int32_t prefetch_ahead;   // ... for the items up to this far beyond the head of their XCD's queue
   int32_t prefetch_behind;  // ... and this far before it (handed out, probably not started yet)

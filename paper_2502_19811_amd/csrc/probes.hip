@@ -1,5 +1,7 @@
 // Measurement aids: the device's own ceilings, measured with the same instructions the GroupGEMM uses, so that
 // the layer's figures can be read against what this board sustains and not only against the published peak.
+#include <type_traits>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -45,14 +47,16 @@ __global__ __launch_bounds__(256) void k_probe_mfma(float* out, int iters) {
   out[blockIdx.x * 256 + threadIdx.x] = sum;
 }
 
-// The MFMA loop again, now with the data movement of a GroupGEMM K step around it, so that the price of each kind of
-// traffic can be read off in TFLOP/s at the board's power limit: per 16 MFMAs of a wavefront (a half K step of the
-// 256 x 256 tile) optionally 8 ds_read_b128 that refresh the operand fragments from LDS (random bf16 data), 4
-// global -> LDS loads of 1 KiB (a workgroup's 16 KiB per half step, from a 2 MiB region that stays in the L2 -- or,
-// STREAM, one load in four from a region of 4 MiB per workgroup that is streamed through, i.e. from HBM), and a
-// workgroup barrier.  No wait depends on the loads except a bound on how many are in flight.
+// The MFMA loop again, now with the data movement of a GroupGEMM K step around it, arranged as the GroupGEMM's main
+// loop arranges it, so that the price of each kind of traffic can be read off, in TFLOP/s, core clock and share of
+// cycles the matrix cores are busy: per 16 MFMAs of a wavefront (a half K step of the 256 x 256 tile, in 4 groups of 4
+// MFMAs) optionally 8 ds_read_b128 that fetch the operand fragments of the next half step from LDS into the other of
+// two register sets (random bf16 data; two reads per group), 4 global -> LDS loads of 1 KiB (one per group: a
+// workgroup's 16 KiB per half step, from a 2 MiB region that stays in the L2 -- or, STREAM, one load in four from a
+// region of 4 MiB per workgroup that is streamed through, i.e. from HBM), and a workgroup barrier every second half
+// step.  No wait depends on the loads except a bound on how many are in flight.
 template <bool LDS_READS, bool DMA, bool BARRIER, bool STREAM>
-__global__ __launch_bounds__(256, 1) void k_probe_mix(const char* __restrict__ gsrc, float* out, int iters) {
+__global__ __launch_bounds__(256, 1) void k_probe_mix(const char* __restrict__ gsrc, float* out, uint64_t* clk, int iters) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];   // 64 KiB of operand data + 32 KiB landing zone
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   uint32_t s = 12345u + tid * 2654435761u + blockIdx.x * 40503u;
@@ -66,11 +70,11 @@ __global__ __launch_bounds__(256, 1) void k_probe_mix(const char* __restrict__ g
   __syncthreads();
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
   auto lds_frag = [](uint32_t a) { return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a; };
-  bf16x8 a[4], b[4];
+  bf16x8 a[2][4], b[2][4];
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    a[i] = lds_frag(lds0 + (w * 8 + i) * 1024 + lane * 16);
-    b[i] = lds_frag(lds0 + (w * 8 + 4 + i) * 1024 + lane * 16);
+    a[0][i] = a[1][i] = lds_frag(lds0 + (w * 8 + i) * 1024 + lane * 16);
+    b[0][i] = b[1][i] = lds_frag(lds0 + (w * 8 + 4 + i) * 1024 + lane * 16);
   }
   f32x16 c[4][4];
 #pragma unroll
@@ -81,28 +85,47 @@ __global__ __launch_bounds__(256, 1) void k_probe_mix(const char* __restrict__ g
   const uint32_t land = lds0 + 65536 + w * 8192;          // and lands its loads in its own 8 KiB
   const uint32_t goff = (uint32_t)(blockIdx.x & 31) * 65536u + w * 16384 + lane * 16;
   const char* stream_base = gsrc + ((size_t)4 << 20) + (size_t)blockIdx.x * ((size_t)4 << 20);
-  for (int it = 0; it < iters; it++) {
+  // one half step: the MFMAs of register set `cur`, the fragments of the next half step into set `nxt`
+  auto half_step = [&](int it, auto cur_c, auto nxt_c) {
+    constexpr int cur = decltype(cur_c)::value, nxt = decltype(nxt_c)::value;
 #pragma unroll
-    for (int m = 0; m < 16; m++) {
-      const int i = m >> 2, j = m & 3;
-      c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], c[i][j], 0, 0, 0);
-      if (LDS_READS && (m & 1) == 0) {
-        const int which = m >> 1;
-        const bf16x8 v = lds_frag(rd + ((it * 8 + which) & 15) * 1024);
-        if (which < 4) a[which] = v; else b[which - 4] = v;
-      }
-      if (DMA && (m & 3) == 0) {
-        const int q = m >> 2;
+    for (int q = 0; q < 4; q++) {
+      if (q > 0) __builtin_amdgcn_sched_barrier(0);
+      if (DMA) {
         const char* base = (STREAM && q == 0) ? stream_base : gsrc + (size_t)((it & 3) * 4096);
         const uint32_t off = (STREAM && q == 0) ? (uint32_t)((it * 4096) & ((4 << 20) - 1)) + w * 1024 + lane * 16 : goff + q * 1024;
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(land + q * 1024)
                      : "memory");
       }
+      if (LDS_READS) {
+        a[nxt][q] = lds_frag(rd + ((it * 8 + q) & 15) * 1024);
+        b[nxt][q] = lds_frag(rd + ((it * 8 + 4 + q) & 15) * 1024);
+      }
+#pragma unroll
+      for (int m = q * 4; m < q * 4 + 4; m++) c[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[cur][m & 3], a[cur][m >> 2], c[m >> 2][m & 3], 0, 0, 0);
+#pragma unroll
+      for (int m = 0; m < 4; m++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (LDS_READS && m < 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
     }
+  };
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, 1>;
+  const uint64_t cycles0 = clock64(), ticks0 = wall_clock64();   // core clock cycles; 100 MHz device clock
+  for (int it = 0; it < iters; it += 2) {
+    half_step(it, C0{}, C1{});
+    __builtin_amdgcn_sched_barrier(0);
     if (DMA) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
     if (BARRIER) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    half_step(it + 1, C1{}, C0{});
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (tid == 0) {
+    clk[blockIdx.x * 2] = clock64() - cycles0;
+    clk[blockIdx.x * 2 + 1] = wall_clock64() - ticks0;
+  }
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; i++)
@@ -173,25 +196,29 @@ int moe_probe_mfma(int32_t random_data, int32_t iters, void* scratch, size_t scr
   return MOE_OK;
 }
 
-int moe_probe_mix(int32_t mode, int32_t iters, void* scratch, size_t scratch_bytes, float* tflops, void* hip_stream) {
+int moe_probe_mix(int32_t mode, int32_t iters, void* scratch, size_t scratch_bytes, float* tflops, float* core_ghz,
+                  void* hip_stream) {
   if (!scratch || !tflops || iters < 1 || iters > (1 << 22) || mode < 0 || mode > 15 || ((uintptr_t)scratch & 15))
     return MOE_ERR_INVALID_ARG;
   const bool lds = mode & 1, dma = mode & 2, bar = mode & 4, stream = mode & 8;
+  iters += iters & 1;   // the loop takes two half steps at a time
   if (stream && !dma) return MOE_ERR_INVALID_ARG;
   const int n_cu = compute_units();
   if (n_cu <= 0) return MOE_ERR_HIP;
   // layout of scratch: 4 MiB that the L2-resident loads read, then (streaming only) 4 MiB per workgroup; the
-  // results land at the start of the first region's last MiB, which no load reads
+  // results land in the first region's last MiB, which no load reads (sums, then the cycle counts 512 KiB further on)
   const size_t need = ((size_t)4 << 20) + (stream ? (size_t)n_cu * ((size_t)4 << 20) : 0);
   if (scratch_bytes < need) return MOE_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)hip_stream;
   const char* g = (const char*)scratch;
   float* out = (float*)((char*)scratch + ((size_t)3 << 20));
+  uint64_t* clk = (uint64_t*)((char*)scratch + ((size_t)3 << 20) + ((size_t)512 << 10));
+  if ((size_t)n_cu * 256 * sizeof(float) > ((size_t)512 << 10) || (size_t)n_cu * 16 > ((size_t)512 << 10)) return MOE_ERR_UNSUPPORTED;
   constexpr int lds_bytes = 96 * 1024;
   auto launch = [&](auto kern) -> hipError_t {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(n_cu), dim3(256), lds_bytes, st, g, out, iters);
+    hipLaunchKernelGGL(kern, dim3(n_cu), dim3(256), lds_bytes, st, g, out, clk, iters);
     return hipGetLastError();
   };
   hipError_t err = hipSuccess;
@@ -208,6 +235,16 @@ int moe_probe_mix(int32_t mode, int32_t iters, void* scratch, size_t scratch_byt
   if (err != hipSuccess || ms <= 0.f) return MOE_ERR_HIP;
   const double flop = (double)n_cu * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
   *tflops = (float)(flop / (ms * 1e-3) / 1e12);
+  if (core_ghz) {
+    // core clock inside the loop: cycles over elapsed time (100 MHz ticks), mean over the workgroups
+    uint64_t host[512 * 2];
+    if (n_cu > 512) return MOE_ERR_UNSUPPORTED;
+    if (hipMemcpyAsync(host, clk, (size_t)n_cu * 16, hipMemcpyDeviceToHost, st) != hipSuccess) return MOE_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return MOE_ERR_HIP;
+    double sum = 0;
+    for (int i = 0; i < n_cu; i++) sum += host[2 * i + 1] ? (double)host[2 * i] / ((double)host[2 * i + 1] * 10.0) : 0.0;
+    *core_ghz = (float)(sum / n_cu);
+  }
   return MOE_OK;
 }
 

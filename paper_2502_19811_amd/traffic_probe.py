@@ -27,23 +27,27 @@ def main() -> int:
     scratch.view(torch.bfloat16).copy_(torch.rand(scratch.numel() // 2, device="cuda", dtype=torch.float32).sub_(0.5)
                                        .to(torch.bfloat16))
     iters = 400000
-    rows = [("MFMA loop, zeros", lambda: moe.moe_probe_mfma(False, iters // 4, scratch)),
-            ("MFMA loop, random bf16", lambda: moe.moe_probe_mfma(True, iters // 4, scratch)),
-            ("mix 0: MFMA only (random bf16 from LDS)", lambda: moe.moe_probe_mix(0, iters, scratch)),
-            ("mix 1: + LDS fragment reads", lambda: moe.moe_probe_mix(1, iters, scratch)),
-            ("mix 3: + global->LDS loads, L2-resident", lambda: moe.moe_probe_mix(3, iters, scratch)),
-            ("mix 7: + workgroup barrier per half step", lambda: moe.moe_probe_mix(7, iters, scratch)),
-            ("mix 11: loads with a quarter from HBM, no barrier", lambda: moe.moe_probe_mix(11, iters, scratch)),
-            ("mix 15: everything", lambda: moe.moe_probe_mix(15, iters, scratch)),
-            ("MFMA loop, random bf16 (again)", lambda: moe.moe_probe_mfma(True, iters // 4, scratch))]
-    print("| loop | TFLOP/s | of the random-data MFMA loop |")
-    print("|---|---|---|")
+    mix = lambda mode: (lambda: moe.moe_probe_mix(mode, iters, scratch, with_clock=True))
+    rows = [("MFMA loop, zeros", lambda: (moe.moe_probe_mfma(False, iters // 4, scratch), None)),
+            ("MFMA loop, random bf16", lambda: (moe.moe_probe_mfma(True, iters // 4, scratch), None)),
+            ("mix 0: MFMA only (random bf16 from LDS)", mix(0)),
+            ("mix 1: + LDS fragment reads", mix(1)),
+            ("mix 3: + global->LDS loads, L2-resident", mix(3)),
+            ("mix 7: + workgroup barrier per half step", mix(7)),
+            ("mix 11: loads with a quarter from HBM, no barrier", mix(11)),
+            ("mix 15: everything", mix(15)),
+            ("MFMA loop, random bf16 (again)", lambda: (moe.moe_probe_mfma(True, iters // 4, scratch), None))]
+    print("| loop | TFLOP/s | of the random-data MFMA loop | core clock GHz | matrix cores busy |")
+    print("|---|---|---|---|---|")
     base = None
     for name, fn in rows:
-        v = fn()
+        v, ghz = fn()
         if name.startswith("MFMA loop, random") and base is None:
             base = v
-        print(f"| {name} | {v:.0f} | {v / base:.3f} |" if base else f"| {name} | {v:.0f} | |", flush=True)
+        rel = f"{v / base:.3f}" if base else ""
+        # a SIMD issues one 32x32x16 MFMA (32768 flop) per 32 cycles: 1024 flop per cycle
+        busy = f"{v * 1e12 / (n_cu * 4 * ghz * 1e9 * 1024):.2f}" if ghz else ""
+        print(f"| {name} | {v:.0f} | {rel} | {ghz:.2f} | {busy} |" if ghz else f"| {name} | {v:.0f} | {rel} | | |", flush=True)
     return 0
 
 

@@ -43,11 +43,11 @@ def test_plan_create_and_options():
     for key, val in [("tile_m", 128), ("n_dm", 7), ("layer0_order", 1), ("layer1_order", 2), ("layer1_order", 0), ("spin_limit", 1000),
                      ("phases", 3), ("n_cu", 64), ("large_schedule", 1), ("block_m", 8),
                      ("layer0_order", 2), ("layer0_waves", 4), ("expected_ingest_gbps", 50), ("weights_packed", 1), ("alias_experts", 1), ("handoff_fences", 1), ("fuse_layers", 1), ("publish_every", 4),
-                     ("n_prefetch", 16), ("prefetch_ahead", 32), ("prefetch_behind", 0)]:
+                     ("n_prefetch", 16), ("prefetch_ahead", 32), ("prefetch_behind", 0), ("deep_short_tiles", 0)]:
         moe.moe_plan_set_option(plan, key, val)
         assert moe.moe_plan_get_option(plan, key) == val
     for key, val in [("tile_m", 100), ("n_dm", -2), ("layer0_order", 3), ("layer0_order", -2), ("layer0_waves", 9), ("phases", 16), ("large_schedule", 2),
-                     ("block_m", 0), ("block_m", 9), ("n_prefetch", 12), ("n_prefetch", 72), ("prefetch_ahead", -1), ("no_such_key", 1)]:
+                     ("block_m", 0), ("block_m", 9), ("n_prefetch", 12), ("n_prefetch", 72), ("prefetch_ahead", -1), ("deep_short_tiles", 2), ("no_such_key", 1)]:
         with pytest.raises(moe.MoEError) as e:
             moe.moe_plan_set_option(plan, key, val)
         assert e.value.status == -1

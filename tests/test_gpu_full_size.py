@@ -134,7 +134,7 @@ def test_full_size_variants_give_the_same_bits():
     for opts, packed in (({"layer1_order": 1, "n_dm": 16}, False), ({"layer1_order": 1, "n_dm": 0}, False),
                          ({"layer0_order": 1}, False), ({}, True), ({"tile_m": 128}, False),
                          ({"fuse_layers": 1, "spin_limit": 1 << 18}, True), ({"layer1_order": 2}, True),
-                         ({"n_prefetch": 8}, True)):
+                         ({"n_prefetch": 8}, True), ({"deep_short_tiles": 0}, True)):
         print(f"  options {opts} packed {packed}", flush=True)
         run = _run(cfg, inp, ids, w, opts, packed)
         np.testing.assert_array_equal(run.out, base.out)
@@ -153,7 +153,8 @@ def test_prefetching_workgroups_leave_the_output_unchanged():
     base = _run(cfg, inp, ids, w, {}, True)
     for opts in ({"n_prefetch": 8}, {"n_prefetch": 16, "prefetch_ahead": 4, "prefetch_behind": 0},
                  {"n_prefetch": 32, "prefetch_ahead": 64, "prefetch_behind": 32}, {"n_prefetch": 8, "layer0_order": 1},
-                 {"n_prefetch": 16, "n_cu": 64}, {"n_prefetch": 8, "layer1_order": 2}):
+                 {"n_prefetch": 16, "n_cu": 64}, {"n_prefetch": 8, "layer1_order": 2}, {"deep_short_tiles": 0},
+                 {"deep_short_tiles": 0, "tile_m": 64}, {"tile_m": 64}):
         print(f"  options {opts}", flush=True)
         run = _run(cfg, inp, ids, w, opts, True)
         np.testing.assert_array_equal(run.out, base.out)
