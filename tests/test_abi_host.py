@@ -40,6 +40,9 @@ def test_plan_create_and_options():
     plan = _create()
     assert moe.moe_plan_workspace_bytes(plan) > 256 * (512 + 256) * 2           # holds h [R,F] and Y [R,H], R = 256
     assert moe.moe_plan_get_option(plan, "tile_m") in (64, 128, 256)
+    # defaults that come from measurements: no prefetching workgroups, deep operand rings for the short tiles
+    assert moe.moe_plan_get_option(plan, "n_prefetch") == 0 and moe.moe_plan_get_option(plan, "deep_short_tiles") == 1
+    assert moe.moe_plan_get_option(plan, "n_dm") == 0 and moe.moe_plan_get_option(plan, "layer1_order") == 0
     for key, val in [("tile_m", 128), ("n_dm", 7), ("layer0_order", 1), ("layer1_order", 2), ("layer1_order", 0), ("spin_limit", 1000),
                      ("phases", 3), ("n_cu", 64), ("large_schedule", 1), ("block_m", 8),
                      ("layer0_order", 2), ("layer0_waves", 4), ("expected_ingest_gbps", 50), ("weights_packed", 1), ("alias_experts", 1), ("handoff_fences", 1), ("fuse_layers", 1), ("publish_every", 4),

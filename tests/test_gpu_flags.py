@@ -251,6 +251,11 @@ def test_device_probes_report_plausible_ceilings():
     mix = moe.moe_probe_mix(7, 4000, big)                       # LDS reads, L2-resident loads, barrier
     print(f"mfma loop with a K step's data movement: {mix:.0f} TFLOP/s", flush=True)
     assert 300.0 < mix < 2600.0
+    tf, ghz = moe.moe_probe_mix(7, 40000, big, with_clock=True)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    busy = tf * 1e12 / (n_cu * 4 * ghz * 1e9 * 1024)           # a SIMD does 1024 flop per cycle with this instruction
+    print(f"  core clock inside the loop {ghz:.2f} GHz, matrix cores busy {busy:.2f}", flush=True)
+    assert 0.5 < ghz < 2.6 and 0.3 < busy < 1.05
     with pytest.raises(moe.MoEError):
         moe.moe_probe_mix(15, 4000, big)                        # streaming needs 4 MiB per compute unit
     with pytest.raises(moe.MoEError):
