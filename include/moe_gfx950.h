@@ -251,17 +251,19 @@ int moe_plan_forward_times(moe_plan_t *plan, float *ms, int32_t capacity, int32_
  * and wait for their own work to finish.
  * moe_probe_mfma: a register-only loop of v_mfma_f32_32x32x16_bf16, 16 accumulator blocks per wavefront, one
  *   workgroup of 4 wavefronts per compute unit, iters x 16 instructions per wavefront; random_data != 0: random bf16
- *   operands, else zeros (zeros draw less power and clock higher).  scratch: dev, at least compute units x 1 KiB
+ *   operands, else zeros (zeros draw less power and clock higher); random_data == 2: random operands and the same
+ *   flop as 64 accumulator blocks of v_mfma_f32_16x16x32_bf16 (half the accumulator traffic per flop).  scratch: dev, at least compute units x 1 KiB
  *   (overwritten).  tflops: host [1].
  * moe_probe_copy: plain device copy of bytes (multiple of 16, both pointers 16-byte aligned) from src to dst;
  *   gbytes_per_s: host [1], bytes read plus bytes written per second.
- * moe_probe_mix: the same MFMA loop on random data with the data movement of a GroupGEMM K step around it, to price
- *   each kind of traffic at the board's power limit: mode is a bit mask -- 1: 8 ds_read_b128 per 16 MFMAs fetch the
- *   operand fragments of the next 16 from LDS into a second register set; 2: 4 global->LDS loads of 1 KiB per 16
- *   MFMAs from an L2-resident region; 4: a workgroup barrier per 32 MFMAs (a K step); 8 (needs 2): one load in four
- *   streams from HBM instead.  The loop runs twice
- *   (warm-up, then timed), iters x 16 MFMAs per wavefront each.  scratch: dev, 16-byte aligned, at least 4 MiB, with
- *   bit 8 at least 4 MiB x (compute units + 1); its contents are read as operands and partly overwritten.
+ * moe_probe_mix: the same MFMA loop on random data with the data movement of a GroupGEMM K step around it, arranged as
+ *   the GroupGEMM's main loop is, to price each kind of traffic: mode is a bit mask -- 1: 16 ds_read_b128 per K step
+ *   (32 MFMAs of a wavefront) fetch the operand fragments of the next (half) step from LDS into a second register set;
+ *   2: 8 global->LDS loads of 1 KiB per K step from an L2-resident region; 4: a workgroup barrier per K step; 8 (needs
+ *   2): two loads in eight stream from HBM instead; 16: the MFMAs are 64 v_mfma_f32_16x16x32_bf16 per K step instead
+ *   of 32 v_mfma_f32_32x32x16_bf16.  The loop runs twice (warm-up, then timed), iters K steps each.  scratch: dev,
+ *   16-byte aligned, at least 4 MiB, with bit 8 at least 4 MiB x (compute units + 1); its contents are read as
+ *   operands and partly overwritten.
  *   tflops: host [1].  core_ghz: host [1] or NULL: the core clock inside the loop (cycle counter over the 100 MHz
  *   device clock, mean over the workgroups), which tells a loop that runs slower because the board clocks lower from
  *   one whose matrix cores wait: busy share = tflops / (compute units x 4 x core_ghz x 1024 flop per cycle). */

@@ -240,17 +240,18 @@ def moe_plan_forward_times(plan: int, capacity: int = 256):
     return [float(ms[i]) for i in range(n.value)]
 
 
-def moe_probe_mfma(random_data: bool, iters: int, scratch, stream=None) -> float:
-    """TFLOP/s of the library's register-only bf16 MFMA loop on this device (scratch: a device tensor of >= 1 MiB)."""
+def moe_probe_mfma(random_data, iters: int, scratch, stream=None) -> float:
+    """TFLOP/s of the library's register-only bf16 MFMA loop on this device (scratch: a device tensor of >= 1 MiB).
+    random_data: False zeros, True random operands, 2 random operands with the 16x16x32 instruction."""
     out = C.c_float()
-    _check(load_library().moe_probe_mfma(int(bool(random_data)), iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
+    _check(load_library().moe_probe_mfma(int(random_data), iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
                                          C.byref(out), _stream(stream)), "moe_probe_mfma")
     return float(out.value)
 
 
 def moe_probe_mix(mode: int, iters: int, scratch, stream=None, with_clock: bool = False):
     """TFLOP/s of the MFMA loop with GroupGEMM-like data movement around it (mode bits: 1 LDS reads, 2 global->LDS
-    loads, 4 barrier, 8 a quarter of the loads from HBM); scratch: a device tensor, see the header for its size.
+    loads, 4 barrier, 8 a quarter of the loads from HBM, 16 the 16x16x32 instruction); iters K steps; scratch: a device tensor, see the header for its size.
     with_clock: returns (TFLOP/s, core clock in GHz inside the loop)."""
     out, ghz = C.c_float(), C.c_float()
     _check(load_library().moe_probe_mix(mode, iters, _ptr(scratch), scratch.numel() * scratch.element_size(),

@@ -26,17 +26,22 @@ def main() -> int:
     # random bytes are not all finite bf16 values: overwrite with a small-valued bf16 pattern
     scratch.view(torch.bfloat16).copy_(torch.rand(scratch.numel() // 2, device="cuda", dtype=torch.float32).sub_(0.5)
                                        .to(torch.bfloat16))
-    iters = 400000
+    iters = 200000   # K steps (32 x 32768 flop per wavefront each)
     mix = lambda mode: (lambda: moe.moe_probe_mix(mode, iters, scratch, with_clock=True))
-    rows = [("MFMA loop, zeros", lambda: (moe.moe_probe_mfma(False, iters // 4, scratch), None)),
-            ("MFMA loop, random bf16", lambda: (moe.moe_probe_mfma(True, iters // 4, scratch), None)),
+    rows = [("MFMA loop, zeros", lambda: (moe.moe_probe_mfma(False, iters // 2, scratch), None)),
+            ("MFMA loop, random bf16", lambda: (moe.moe_probe_mfma(True, iters // 2, scratch), None)),
             ("mix 0: MFMA only (random bf16 from LDS)", mix(0)),
             ("mix 1: + LDS fragment reads", mix(1)),
             ("mix 3: + global->LDS loads, L2-resident", mix(3)),
-            ("mix 7: + workgroup barrier per half step", mix(7)),
+            ("mix 7: + workgroup barrier per K step", mix(7)),
             ("mix 11: loads with a quarter from HBM, no barrier", mix(11)),
             ("mix 15: everything", mix(15)),
-            ("MFMA loop, random bf16 (again)", lambda: (moe.moe_probe_mfma(True, iters // 4, scratch), None))]
+            ("MFMA loop, random bf16 (again)", lambda: (moe.moe_probe_mfma(True, iters // 2, scratch), None)),
+            ("16x16x32 MFMA loop, random bf16", lambda: (moe.moe_probe_mfma(2, iters // 2, scratch), None)),
+            ("16x16x32 mix 16: MFMA only", mix(16)),
+            ("16x16x32 mix 17: + LDS fragment reads", mix(17)),
+            ("16x16x32 mix 23: + loads from the L2 and barrier", mix(23)),
+            ("16x16x32 mix 31: everything", mix(31))]
     print("| loop | TFLOP/s | of the random-data MFMA loop | core clock GHz | matrix cores busy |")
     print("|---|---|---|---|---|")
     base = None
