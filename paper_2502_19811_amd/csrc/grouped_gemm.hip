@@ -629,8 +629,51 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // the vector-memory queue and stall the MFMAs queued behind it.
   using P0 = std::integral_constant<int, 0>;
   using P1 = std::integral_constant<int, 1>;
-  // LDS offset of the A block that holds row half hh for K step `step`
-  auto a_slot = [&](int step, int hh) { return (uint32_t)((2 * (step >> 1) + hh) % AB) * A_BLOCK; };
+  // Where K step kt finds its operands in the rings and where its loads go, kept incrementally: written as
+  // (kt ...) % AB the compiler turns the read addresses into per-lane vectors that it rebases every step, and the
+  // scalar divisions pile up at the top of the loop, where no MFMA covers them (2 % of the kernel's time).
+  struct Ring {
+    uint32_t oa, ob;      // LDS offsets of the A block of row half 0 of kt's pair of steps and of B stage kt
+    uint32_t a0, a1;      // A blocks of step kt, row halves 0 and 1 (LDS offsets)
+    uint32_t an0, an1;    // ... of step kt + 1
+    uint32_t b, bn;       // B stage kt, kt + 1
+    uint32_t adst, bdst;  // slots of A block kt + LEAD and B stage kt + LEAD
+  };
+  auto wrap_a = [](uint32_t x) { return x >= (uint32_t)AB * A_BLOCK ? x - (uint32_t)AB * A_BLOCK : x; };
+  auto wrap_b = [](uint32_t x) { return x >= (uint32_t)NSX * B_STAGE ? x - (uint32_t)NSX * B_STAGE : x; };
+  // The state of the step after r's, whose parity is PARNEW: the A ring's part and the B ring's part (worked out in
+  // different groups of MFMAs, see half1 and half2).
+  auto advance_a = [&](const Ring& r, Ring& n, auto parnew) {
+    constexpr int PARNEW = decltype(parnew)::value;
+    n.oa = PARNEW == 0 ? wrap_a(r.oa + 2 * A_BLOCK) : r.oa;   // an even step begins a new pair of A blocks
+    n.a0 = r.an0;
+    n.a1 = r.an1;
+    if (PARNEW == 0) {
+      n.an0 = n.a0;
+      n.an1 = n.a1;
+    } else {
+      n.an0 = wrap_a(n.oa + 2 * A_BLOCK);
+      n.an1 = wrap_a(n.oa + 3 * A_BLOCK);
+    }
+    n.adst = wrap_a(n.oa + (uint32_t)(LEAD + PARNEW) * A_BLOCK);
+  };
+  auto advance_b = [&](const Ring& r, Ring& n) {
+    n.ob = wrap_b(r.ob + B_STAGE);
+    n.b = r.bn;
+    n.bn = wrap_b(n.ob + B_STAGE);
+    n.bdst = wrap_b(n.ob + (uint32_t)LEAD * B_STAGE);
+  };
+  Ring ring, next_ring;   // K step 0; the step after it (filled in as the step goes)
+  ring.oa = 0;
+  ring.ob = 0;
+  ring.a0 = ring.an0 = 0;
+  ring.a1 = ring.an1 = A_BLOCK;
+  ring.b = 0;
+  ring.bn = B_STAGE;
+  ring.adst = (uint32_t)LEAD * A_BLOCK;
+  ring.bdst = (uint32_t)LEAD * B_STAGE;
+  next_ring = ring;
+  const char* a_src = Ab + ((LEAD - 1) / 2) * 128;   // what the A block of an even step is loaded from; + 128: of the odd step after it
   // where fragment q (32 rows) of this wavefront sits: row half and offset inside the block
   auto frag_off = [&](const uint32_t (&blk)[2], int q) {
     const int f = wm * MT + q;   // WM == 2: f / FPB == wm for every q
@@ -672,32 +715,37 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   };
   // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+LEAD
-  auto half1 = [&](auto par, int kt, bool do_issue) {
+  auto half1 = [&](auto par, bool do_issue) {
     constexpr int PAR = decltype(par)::value;
-    const uint32_t blk[2] = {a_slot(kt, 0), a_slot(kt, 1)};
-    const uint32_t b_off = (uint32_t)(kt % NSX) * B_STAGE;
-    const int b = kt + LEAD;
-    const char* src = Ab + (b >> 1) * 128;
-    const uint32_t dst = lds0 + (uint32_t)(b % AB) * A_BLOCK + w * LA * 1024;
+    const uint32_t blk[2] = {ring.a0, ring.a1};
+    const uint32_t b_off = ring.b;
+    const char* src = a_src + PAR * 128;
+    const uint32_t dst = lds0 + ring.adst + w * LA * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
       if (do_issue && q < LA) dma16(src, ls.aoff[((PAR + LEAD) & 1) * LA + q], dst + q * 1024);
+      if (q == 3) advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});   // under this group's MFMAs
       group(0, 1, blk, b_off, PAR, 1, q);
     }
   };
-  // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+LEAD
-  auto half2 = [&](auto par, int kt, bool do_issue) {
+  // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+LEAD; the last
+  // groups of both halves also work out where the next step finds its operands, so that this is done under MFMAs
+  auto half2 = [&](auto par, bool do_issue) {
     constexpr int PAR = decltype(par)::value;
-    const uint32_t blk[2] = {a_slot(kt + 1, 0), a_slot(kt + 1, 1)};
-    const uint32_t b_off = (uint32_t)((kt + 1) % NSX) * B_STAGE;
-    const uint32_t dst = lds0 + B_RING + (uint32_t)((kt + LEAD) % NSX) * B_STAGE + w * LB * 1024;
+    const uint32_t blk[2] = {ring.an0, ring.an1};
+    const uint32_t b_off = ring.bn;
+    const uint32_t dst = lds0 + B_RING + ring.bdst + w * LB * 1024;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);
       if (do_issue && q < LB) dma16(Bb, ls.boff[q], dst + q * 1024);
+      if (q == 3) advance_b(ring, next_ring);
       group(1, 0, blk, b_off, 1 - PAR, 0, q);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    ring = next_ring;
+    if (PAR == 1) a_src += 128;
   };
 
   // The next item of this XCD's queue is requested before anything else of this tile is outstanding; the
@@ -722,7 +770,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   MOE_TRACE_STAMP(tt1);
   MOE_TRACE_CYCLES(tc_loop);
   {
-    const uint32_t blk[2] = {a_slot(0, 0), a_slot(0, 1)};
+    const uint32_t blk[2] = {ring.a0, ring.a1};
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) af[0][mt] = lds_read_a(frag_off(blk, mt) + a_rd[0][0]);
   }
@@ -731,7 +779,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 
   int kt = 0;
   auto step = [&](auto par) {
-    half1(par, kt, true);
+    half1(par, true);
     // B stage kt+1 and the A blocks of step kt+1 (up to block kt+2) have landed for this lane; younger, in issue
     // order: B stage kt+2, blocks and stages kt+3 .. kt+LEAD-1, A block kt+LEAD: LEAD-2 steps' worth of loads.
     // After the barrier they have for all, and all are done reading step kt.  The scheduler must not move MFMAs of the
@@ -742,7 +790,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     block_barrier();
     MOE_TRACE_ADD_CYCLES(tc_sync, tc_mark);
     __builtin_amdgcn_sched_barrier(0);
-    half2(par, kt, true);
+    half2(par, true);
     Bb += bstep;
     kt++;
   };
@@ -757,27 +805,27 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   // is younger than the loads the step waits for is B stage kt+2 and the blocks and stages of the r-2 steps after it.
   static_assert(LEAD == 3 || LEAD == 5, "the steps without loads are written out for these two");
   if constexpr (LEAD == 5) {
-    half1(P1{}, kt, false);
+    half1(P1{}, false);
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<LB + 2 * LS>();
     block_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    half2(P1{}, kt, false);
+    half2(P1{}, false);
     kt++;
-    half1(P0{}, kt, false);
+    half1(P0{}, false);
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<LB + LS>();
     block_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    half2(P0{}, kt, false);
+    half2(P0{}, false);
     kt++;
   }
-  half1(P1{}, kt, false);
+  half1(P1{}, false);
   wait_vmcnt<LB>();   // younger than the last A block: the last B stage
   block_barrier();
-  half2(P1{}, kt, false);
+  half2(P1{}, false);
   kt++;
-  half1(P0{}, kt, false);
+  half1(P0{}, false);
   wait_vmcnt<0>();
   // No operand load is in flight any more, so memory operations the compiler waits for by itself no longer stall
   // behind them: thread 0 turns its queue ticket into a list position (stealing from other XCDs if its own queue is
@@ -799,9 +847,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     ready_mask = (uint32_t)uniform((int)lds_mask[0]) | ((uint64_t)(uint32_t)uniform((int)lds_mask[1]) << 32);
   ItemRec raw_rec;
   if (next.idx >= 0) raw_rec = p.items[next.idx];
-  half2(P0{}, kt, false);
+  half2(P0{}, false);
   kt++;
-  half1(P1{}, kt, false);
+  half1(P1{}, false);
 #pragma unroll
   for (int mt = 0; mt < MT; mt++)
 #pragma unroll
