@@ -601,6 +601,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
       if (PK) {
         // column block of the packed tile this wavefront's block nt is: SwiGLU tiles hold [4 gate | 4 up] blocks of the
         // same 128 hidden units, of which a wavefront takes the gate and up blocks of its own units
+        // (block nt lies a constant number of KiB behind block 0: b_block_offset below)
         const int c = MODE == MODE_L0_SWIGLU ? (nt / (NT / 2)) * 4 + wn * (NT / 2) + nt % (NT / 2) : wn * NT + nt;
         b_rd[nt] = lds0 + B_RING + c * 1024 + lane * 16;
       } else {
@@ -679,10 +680,30 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const int f = wm * MT + q;   // WM == 2: f / FPB == wm for every q
     return (WM == 2 ? (wm ? blk[1] : blk[0]) : blk[f / FPB]) + (uint32_t)(f % FPB) * (32 * 128);
   };
+  // The read addresses of a half step as one per-lane base per operand plus constants that go into the instructions'
+  // offset fields: one address addition per operand and half step instead of one per fragment.
+  //   A: the block (or, 64-row tiles, the two blocks) the wavefront's fragments lie in; fragment q is q * 4 KiB further on
+  //   B (packed): block 0 of the wavefront; block nt is b_block_offset(nt) further on
+  struct HalfBases { uint32_t a[2], b; };
+  auto half_bases = [&](const uint32_t (&blk)[2], uint32_t b_off, int rd_par, int rd_kk) {
+    HalfBases hb;
+    hb.a[0] = (WM == 2 ? (wm ? blk[1] : blk[0]) : blk[0]) + a_rd[rd_par][rd_kk];
+    hb.a[1] = WM == 2 ? hb.a[0] : blk[1] + a_rd[rd_par][rd_kk];
+    hb.b = b_off + b_rd[0] + rd_kk * (B_STAGE / 2);
+    return hb;
+  };
+  auto a_frag_addr = [&](const HalfBases& hb, int q) {
+    // WM == 2: f = wm * MT + q lies in block wm at position q (MT == FPB); WM == 1: fragment q is block q / FPB
+    return WM == 2 ? hb.a[0] + (uint32_t)q * (32 * 128) : hb.a[q / FPB] + (uint32_t)(q % FPB) * (32 * 128);
+  };
+  auto b_block_offset = [](int nt) {
+    return (uint32_t)(MODE == MODE_L0_SWIGLU ? (nt / (NT / 2)) * 4 + nt % (NT / 2) : nt) * 1024;
+  };
+  static_assert(WM == 1 || MT == FPB, "a wavefront's fragments fill one A block");
   bf16x8 af[2][MT], bfr[2][NT];
   // Group q (of 4) of a half step: the LDS reads of fragment q for the next half step and a quarter of the MFMAs
   // of this one.  blk / b_off / rd_par / rd_kk: A blocks, B stage, parity and 16-deep half of the step read from.
-  auto group = [&](int cb, int nb, const uint32_t (&blk)[2], uint32_t b_off, int rd_par, int rd_kk, int q) {
+  auto group = [&](int cb, int nb, const HalfBases& hb, uint32_t b_off, int rd_kk, int q) {
     constexpr int PER = MT * NT / 4;
     // The fragments of the next half step are all requested in the first kReadGroups groups, so that they are back
     // well before the half step ends: the workgroup barrier between the halves waits for every outstanding LDS
@@ -691,11 +712,11 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int f = q * kFragsPerGroup; f < (q + 1) * kFragsPerGroup; f++) {
       if (q < kReadGroups && f < MT) {
-        af[nb][f] = lds_read_a(frag_off(blk, f) + a_rd[rd_par][rd_kk]);
+        af[nb][f] = lds_read_a(a_frag_addr(hb, f));
         n_reads += 1;
       }
       if (q < kReadGroups && f < NT) {
-        if (PK) bfr[nb][f] = lds_read_b_packed(b_off + b_rd[f] + rd_kk * (B_STAGE / 2));
+        if (PK) bfr[nb][f] = lds_read_b_packed(hb.b + b_block_offset(f));
         else bfr[nb][f] = lds_read_b(b_off + b_rd[f] + rd_kk * 16 * 512, b_off + b_rd[f] + (rd_kk * 16 + 4) * 512);
         n_reads += PK ? 1 : 2;
       }
@@ -721,12 +742,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const uint32_t b_off = ring.b;
     const char* src = a_src + PAR * 128;
     const uint32_t dst = lds0 + ring.adst + w * LA * 1024;
+    const HalfBases hb = half_bases(blk, b_off, PAR, 1);
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
       if (do_issue && q < LA) dma16(src, ls.aoff[((PAR + LEAD) & 1) * LA + q], dst + q * 1024);
       if (q == 3) advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});   // under this group's MFMAs
-      group(0, 1, blk, b_off, PAR, 1, q);
+      group(0, 1, hb, b_off, 1, q);
     }
   };
   // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+LEAD; the last
@@ -736,12 +758,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const uint32_t blk[2] = {ring.an0, ring.an1};
     const uint32_t b_off = ring.bn;
     const uint32_t dst = lds0 + B_RING + ring.bdst + w * LB * 1024;
+    const HalfBases hb = half_bases(blk, b_off, 1 - PAR, 0);
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);
       if (do_issue && q < LB) dma16(Bb, ls.boff[q], dst + q * 1024);
       if (q == 3) advance_b(ring, next_ring);
-      group(1, 0, blk, b_off, 1 - PAR, 0, q);
+      group(1, 0, hb, b_off, 0, q);
     }
     __builtin_amdgcn_sched_barrier(0);
     ring = next_ring;
