@@ -66,6 +66,16 @@ __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base)
                : "memory");
 }
+// The same with the LDS address given as a base in a scalar register plus a constant: the addition writes M0 itself.
+template <int OFF>
+__device__ __forceinline__ void dma16_at(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  if constexpr (OFF == 0) {
+    dma16(sbase, voff, lds_base);
+  } else {
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(OFF)
+                 : "memory", "scc");
+  }
+}
 // Tells the compiler that a pointer / integer is the same in every lane (keeps it in scalar registers).
 __device__ __forceinline__ const char* uniform(const char* ptr) {
   const uint64_t v = (uint64_t)(uintptr_t)ptr;
@@ -641,7 +651,10 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     uint32_t adst, bdst;  // slots of A block kt + LEAD and B stage kt + LEAD
   };
   auto wrap_a = [](uint32_t x) { return x >= (uint32_t)AB * A_BLOCK ? x - (uint32_t)AB * A_BLOCK : x; };
-  auto wrap_b = [](uint32_t x) { return x >= (uint32_t)NSX * B_STAGE ? x - (uint32_t)NSX * B_STAGE : x; };
+  auto wrap_b = [](uint32_t x) {
+    if constexpr ((NSX & (NSX - 1)) == 0) return x & ((uint32_t)NSX * B_STAGE - 1);   // (offsets are multiples of B_STAGE)
+    else return x >= (uint32_t)NSX * B_STAGE ? x - (uint32_t)NSX * B_STAGE : x;
+  };
   // The state of the step after r's, whose parity is PARNEW: the A ring's part and the B ring's part (worked out in
   // different groups of MFMAs, see half1 and half2).
   auto advance_a = [&](const Ring& r, Ring& n, auto parnew) {
@@ -746,7 +759,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
-      if (do_issue && q < LA) dma16(src, ls.aoff[((PAR + LEAD) & 1) * LA + q], dst + q * 1024);
+      if (do_issue && q < LA) {
+        const uint32_t off = ls.aoff[((PAR + LEAD) & 1) * LA + q];
+        if (q == 0) dma16_at<0>(src, off, dst);
+        else if (q == 1) dma16_at<1024>(src, off, dst);
+        else if (q == 2) dma16_at<2048>(src, off, dst);
+        else dma16_at<3072>(src, off, dst);
+      }
       if (q == 3) advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});   // under this group's MFMAs
       group(0, 1, hb, b_off, 1, q);
     }
@@ -762,7 +781,12 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);
-      if (do_issue && q < LB) dma16(Bb, ls.boff[q], dst + q * 1024);
+      if (do_issue && q < LB) {
+        if (q == 0) dma16_at<0>(Bb, ls.boff[q], dst);
+        else if (q == 1) dma16_at<1024>(Bb, ls.boff[q], dst);
+        else if (q == 2) dma16_at<2048>(Bb, ls.boff[q], dst);
+        else dma16_at<3072>(Bb, ls.boff[q], dst);
+      }
       if (q == 3) advance_b(ring, next_ring);
       group(1, 0, hb, b_off, 0, q);
     }
