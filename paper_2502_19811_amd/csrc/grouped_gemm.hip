@@ -38,7 +38,7 @@ enum { MODE_L0_GELU = 0, MODE_L0_SWIGLU = 1, MODE_L1 = 2 };
 
 constexpr int BK = kTileK, NS = kStages, BN = kTileN;
 #ifndef MOE_READ_GROUPS
-#define MOE_READ_GROUPS 4
+#define MOE_READ_GROUPS 2
 #endif
 constexpr int kReadGroups = MOE_READ_GROUPS;        // of the 4 groups of a half step, how many carry the LDS reads
 constexpr int kFragsPerGroup = 4 / kReadGroups;     // fragments (of at most 4 per operand) requested per such group
