@@ -759,6 +759,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
+      if (q == 3) advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});   // under this group's MFMAs
+      group(0, 1, hb, b_off, 1, q);
+      // (behind the group's MFMAs, so that a half step begins with an MFMA and not with the load's set-up)
       if (do_issue && q < LA) {
         const uint32_t off = ls.aoff[((PAR + LEAD) & 1) * LA + q];
         if (q == 0) dma16_at<0>(src, off, dst);
@@ -766,8 +769,6 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
         else if (q == 2) dma16_at<2048>(src, off, dst);
         else dma16_at<3072>(src, off, dst);
       }
-      if (q == 3) advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});   // under this group's MFMAs
-      group(0, 1, hb, b_off, 1, q);
     }
   };
   // second half: MFMAs of the second 16 values, fragments of the first 16 of step kt+1, B stage kt+LEAD; the last
@@ -781,14 +782,14 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);
+      if (q == 3) advance_b(ring, next_ring);
+      group(1, 0, hb, b_off, 0, q);
       if (do_issue && q < LB) {
         if (q == 0) dma16_at<0>(Bb, ls.boff[q], dst);
         else if (q == 1) dma16_at<1024>(Bb, ls.boff[q], dst);
         else if (q == 2) dma16_at<2048>(Bb, ls.boff[q], dst);
         else dma16_at<3072>(Bb, ls.boff[q], dst);
       }
-      if (q == 3) advance_b(ring, next_ring);
-      group(1, 0, hb, b_off, 0, q);
     }
     __builtin_amdgcn_sched_barrier(0);
     ring = next_ring;
