@@ -748,6 +748,13 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     for (int i = PER; i < 12; i++)
       if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   };
+  // read addresses of the half step about to begin (first half of step 0) and of the one after it
+  HalfBases hb_first, hb_second;
+  {
+    const uint32_t blk0[2] = {ring.a0, ring.a1};
+    hb_first = half_bases(blk0, ring.b, 0, 1);
+    hb_second = hb_first;
+  }
   // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+LEAD
   auto half1 = [&](auto par, bool do_issue) {
     constexpr int PAR = decltype(par)::value;
@@ -755,11 +762,16 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const uint32_t b_off = ring.b;
     const char* src = a_src + PAR * 128;
     const uint32_t dst = lds0 + ring.adst + w * LA * 1024;
-    const HalfBases hb = half_bases(blk, b_off, PAR, 1);
+    const HalfBases hb = hb_first;   // worked out under the MFMAs of the half step before
+    (void)blk;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);   // the loads stay where they are written: one per group
-      if (q == 3) advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});   // under this group's MFMAs
+      if (q == 3) {   // under this group's MFMAs: the A ring's next positions, and the read addresses of the second half
+        advance_a(ring, next_ring, std::integral_constant<int, 1 - PAR>{});
+        const uint32_t blk2[2] = {ring.an0, ring.an1};
+        hb_second = half_bases(blk2, ring.bn, 1 - PAR, 0);
+      }
       group(0, 1, hb, b_off, 1, q);
       // (behind the group's MFMAs, so that a half step begins with an MFMA and not with the load's set-up)
       if (do_issue && q < LA) {
@@ -778,11 +790,16 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     const uint32_t blk[2] = {ring.an0, ring.an1};
     const uint32_t b_off = ring.bn;
     const uint32_t dst = lds0 + B_RING + ring.bdst + w * LB * 1024;
-    const HalfBases hb = half_bases(blk, b_off, 1 - PAR, 0);
+    const HalfBases hb = hb_second;
+    (void)blk;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
       if (q > 0) __builtin_amdgcn_sched_barrier(0);
-      if (q == 3) advance_b(ring, next_ring);
+      if (q == 3) {   // the B ring's next positions, and the read addresses of the next step's first half
+        advance_b(ring, next_ring);
+        const uint32_t blk1[2] = {next_ring.a0, next_ring.a1};
+        hb_first = half_bases(blk1, next_ring.b, 1 - PAR, 1);
+      }
       group(1, 0, hb, b_off, 0, q);
       if (do_issue && q < LB) {
         if (q == 0) dma16_at<0>(Bb, ls.boff[q], dst);
