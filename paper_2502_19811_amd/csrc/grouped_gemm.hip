@@ -629,11 +629,9 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   const char* Bb = uniform(ls.Bb);
   const size_t bstep = PK ? (size_t)B_STAGE : (size_t)BK * p.ldb * 2;
 
+  // Not cleared: the MFMAs of the tile's first half step take a zero constant as their addend instead (clearing 256
+  // accumulator registers is 256 instructions, 0.8 us of a tile with the matrix cores idle).
   f32x16 acc[MT][NT];
-#pragma unroll
-  for (int i = 0; i < MT; i++)
-#pragma unroll
-    for (int j = 0; j < NT; j++) acc[i][j] = (f32x16){0};
 
   // Per K step and lane: LA loads of A (block kt+LEAD: the other half of the rows than the block before, 64 values of K)
   // and LB loads of B (stage kt+LEAD).  The loads are issued one at a time between groups of MFMAs: a burst would fill
@@ -716,7 +714,8 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   bf16x8 af[2][MT], bfr[2][NT];
   // Group q (of 4) of a half step: the LDS reads of fragment q for the next half step and a quarter of the MFMAs
   // of this one.  blk / b_off / rd_par / rd_kk: A blocks, B stage, parity and 16-deep half of the step read from.
-  auto group = [&](int cb, int nb, const HalfBases& hb, uint32_t b_off, int rd_kk, int q) {
+  auto group = [&](int cb, int nb, const HalfBases& hb, uint32_t b_off, int rd_kk, int q, auto first) {
+    constexpr bool FIRST = decltype(first)::value;   // the tile's first half step: nothing accumulated yet
     constexpr int PER = MT * NT / 4;
     // The fragments of the next half step are all requested in the first kReadGroups groups, so that they are back
     // well before the half step ends: the workgroup barrier between the halves waits for every outstanding LDS
@@ -737,7 +736,8 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
 #pragma unroll
     for (int i = 0; i < PER; i++) {
       const int m = q * PER + i, mt = m / NT, nt = m % NT;
-      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][nt], af[cb][mt], acc[mt][nt], 0, 0, 0);
+      if constexpr (FIRST) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][nt], af[cb][mt], (f32x16){0}, 0, 0, 0);
+      else acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cb][nt], af[cb][mt], acc[mt][nt], 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < PER; i++) {
@@ -756,7 +756,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     hb_second = hb_first;
   }
   // first half of K step kt (parity PAR): MFMAs of its first 16 values of K, fragments of its second 16, A block kt+LEAD
-  auto half1 = [&](auto par, bool do_issue) {
+  auto half1 = [&](auto par, bool do_issue, auto first) {
     constexpr int PAR = decltype(par)::value;
     const uint32_t blk[2] = {ring.a0, ring.a1};
     const uint32_t b_off = ring.b;
@@ -772,7 +772,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
         const uint32_t blk2[2] = {ring.an0, ring.an1};
         hb_second = half_bases(blk2, ring.bn, 1 - PAR, 0);
       }
-      group(0, 1, hb, b_off, 1, q);
+      group(0, 1, hb, b_off, 1, q, first);
       // (behind the group's MFMAs, so that a half step begins with an MFMA and not with the load's set-up)
       if (do_issue && q < LA) {
         const uint32_t off = ls.aoff[((PAR + LEAD) & 1) * LA + q];
@@ -800,7 +800,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
         const uint32_t blk1[2] = {next_ring.a0, next_ring.a1};
         hb_first = half_bases(blk1, next_ring.b, 1 - PAR, 1);
       }
-      group(1, 0, hb, b_off, 0, q);
+      group(1, 0, hb, b_off, 0, q, std::false_type{});
       if (do_issue && q < LB) {
         if (q == 0) dma16_at<0>(Bb, ls.boff[q], dst);
         else if (q == 1) dma16_at<1024>(Bb, ls.boff[q], dst);
@@ -843,8 +843,8 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   for (int nt = 0; nt < NT; nt++) bfr[0][nt] = PK ? lds_read_b_packed(b_rd[nt]) : lds_read_b(b_rd[nt], b_rd[nt] + 4 * 512);
 
   int kt = 0;
-  auto step = [&](auto par) {
-    half1(par, true);
+  auto step = [&](auto par, auto first) {
+    half1(par, true, first);
     // B stage kt+1 and the A blocks of step kt+1 (up to block kt+2) have landed for this lane; younger, in issue
     // order: B stage kt+2, blocks and stages kt+3 .. kt+LEAD-1, A block kt+LEAD: LEAD-2 steps' worth of loads.
     // After the barrier they have for all, and all are done reading step kt.  The scheduler must not move MFMAs of the
@@ -860,24 +860,24 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     kt++;
   };
   const int kt_end = nk - LEAD;   // odd; at least 1 (the caller picks NSX so that nk > LEAD)
+  step(P0{}, std::true_type{});   // kt_end is odd: an even number of steps with loads follows
   while (kt + 2 <= kt_end) {
-    step(P0{});
-    step(P1{});
+    step(P1{}, std::false_type{});
+    step(P0{}, std::false_type{});
   }
-  if (kt < kt_end) step(P0{});
 
   // The last LEAD steps (parities 1, 0, ..., 1) issue nothing.  With r steps still to come after the current one, what
   // is younger than the loads the step waits for is B stage kt+2 and the blocks and stages of the r-2 steps after it.
   static_assert(LEAD == 3 || LEAD == 5, "the steps without loads are written out for these two");
   if constexpr (LEAD == 5) {
-    half1(P1{}, false);
+    half1(P1{}, false, std::false_type{});
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<LB + 2 * LS>();
     block_barrier();
     __builtin_amdgcn_sched_barrier(0);
     half2(P1{}, false);
     kt++;
-    half1(P0{}, false);
+    half1(P0{}, false, std::false_type{});
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<LB + LS>();
     block_barrier();
@@ -885,12 +885,12 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
     half2(P0{}, false);
     kt++;
   }
-  half1(P1{}, false);
+  half1(P1{}, false, std::false_type{});
   wait_vmcnt<LB>();   // younger than the last A block: the last B stage
   block_barrier();
   half2(P1{}, false);
   kt++;
-  half1(P0{}, false);
+  half1(P0{}, false, std::false_type{});
   wait_vmcnt<0>();
   // No operand load is in flight any more, so memory operations the compiler waits for by itself no longer stall
   // behind them: thread 0 turns its queue ticket into a list position (stealing from other XCDs if its own queue is
@@ -914,7 +914,7 @@ __device__ __forceinline__ void run_tile(const GemmParams& p, char* smem, volati
   if (next.idx >= 0) raw_rec = p.items[next.idx];
   half2(P0{}, false);
   kt++;
-  half1(P1{}, false);
+  half1(P1{}, false, std::false_type{});
 #pragma unroll
   for (int mt = 0; mt < MT; mt++)
 #pragma unroll
