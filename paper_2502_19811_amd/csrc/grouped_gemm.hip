@@ -1102,7 +1102,10 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GemmParams p) {
   __shared__ int32_t lds_panel_count[kMaxPanels];   // layer1, batched publication: tiles finished per column panel
   const int tid = threadIdx.x;
 #ifdef MOE_TILE_TRACE
-  if (tid == 0) lds_mask[2] = lds_mask[3] = 0;
+  if (tid == 0) {   // a workgroup that gets no tile in this launch has noted none
+    lds_mask[2] = lds_mask[3] = 0;
+    if (blockIdx.x < kTraceWgs) g_trace_count[MODE == MODE_L1 ? 1 : 0][blockIdx.x] = 0;
+  }
 #endif
   if (MODE == MODE_L1) {
     for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
@@ -1188,7 +1191,10 @@ __global__ __launch_bounds__(256, 1) void k_fused_layers(GemmParams p0, GemmPara
   __shared__ int32_t lds_tile_cnt[kScheduleTileCap];   // layer0 tiles this workgroup finished per M-tile, not yet published
   const int tid = threadIdx.x;
 #ifdef MOE_TILE_TRACE
-  if (tid == 0) lds_mask[2] = lds_mask[3] = 0;
+  if (tid == 0) {
+    lds_mask[2] = lds_mask[3] = 0;
+    if (blockIdx.x < kTraceWgs) g_trace_count[0][blockIdx.x] = g_trace_count[1][blockIdx.x] = 0;
+  }
 #endif
   for (int i = tid; i < kScheduleTileCap; i += 256) lds_tile_cnt[i] = 0;
   for (int i = tid; i < kMaxPanels; i += 256) lds_panel_count[i] = 0;
