@@ -23,7 +23,7 @@ def bf16_to_np(t: torch.Tensor) -> np.ndarray:
 
 
 @dataclass
-class GpuRun:
+class ForwardResult:
     out: np.ndarray                 # fp64 view of the bf16 output [T,H]
     counts: np.ndarray
     offsets: np.ndarray
@@ -61,7 +61,7 @@ class GpuLayer:
         moe.moe_layer_forward(self.plan, self.x, self.ids, self.w, self.W1, self.W2, self.cfg.act, self.out, self.ws,
                               seg_ready, epoch, stream)
 
-    def results(self) -> GpuRun:
+    def results(self) -> ForwardResult:
         cfg = self.cfg
         i32 = dict(dtype=torch.int32, device="cuda")
         counts = torch.zeros(cfg.E, **i32)
@@ -79,7 +79,7 @@ class GpuLayer:
         n = int(n_tiles.item())
         tiles = {"expert": te[:n].cpu().numpy(), "row0": tr0[:n].cpu().numpy(), "rows": tr[:n].cpu().numpy(),
                  "ready_seg": ts[:n].cpu().numpy(), "height": th[:n].cpu().numpy()}
-        return GpuRun(bf16_to_np(self.out), counts.cpu().numpy(), offsets.cpu().numpy(), perm[:cfg.R].cpu().numpy(),
+        return ForwardResult(bf16_to_np(self.out), counts.cpu().numpy(), offsets.cpu().numpy(), perm[:cfg.R].cpu().numpy(),
                       inv[:cfg.R].cpu().numpy(), tiles, status)
 
     def schedule(self, layer: int):
