@@ -136,6 +136,24 @@ def test_single_expert_is_a_dense_mlp(act):
     np.testing.assert_allclose(got, (h @ W2).numpy(), rtol=1e-11, atol=1e-12)
 
 
+@pytest.mark.parametrize("act", [orc.ACT_GELU, orc.ACT_SWIGLU])
+def test_column_chunks_narrower_than_the_layer(act):
+    """The expert FFN walks W1's columns and W2's rows in chunks; with chunks narrower than F (and a ragged last
+    one) the result is still the dense two-layer MLP of a library matmul."""
+    cfg, inp, _, _ = _small_problem(T=20, H=32, F=88, E=2, k=1, act=act, seed=27)
+    ids = (np.arange(cfg.T) % 2).astype(np.int32).reshape(-1, 1)
+    _, offsets, perm, _ = orc.build_permutation(ids, cfg.E)
+    x = torch.from_numpy(wl.bf16_to_f32(inp.x)).double()
+    for chunk in (24, 40, 4096):
+        Y = orc.expert_ffn(inp.x, inp.W1, inp.W2, offsets, perm, 1, act, round_h=False, col_chunk=chunk)
+        for e in range(cfg.E):
+            W1 = torch.from_numpy(wl.bf16_to_f32(inp.W1[e])).double()
+            W2 = torch.from_numpy(wl.bf16_to_f32(inp.W2[e])).double()
+            G = x[e::2] @ W1
+            h = torch.nn.functional.gelu(G) if act == orc.ACT_GELU else torch.nn.functional.silu(G[:, :cfg.F]) * G[:, cfg.F:]
+            np.testing.assert_allclose(Y[offsets[e]:offsets[e + 1]], (h @ W2).numpy(), rtol=1e-11, atol=1e-12)
+
+
 def test_identity_activation_makes_the_layer_linear():
     cfg, inp, ids, w = _small_problem(T=30, H=20, F=36, E=5, k=3, act=orc.ACT_IDENTITY, seed=23)
     got = orc.moe_layer(inp.x, inp.W1, inp.W2, ids, w, orc.ACT_IDENTITY, round_h=False)

@@ -59,6 +59,17 @@ def test_route_ties_go_to_lower_expert():
     np.testing.assert_allclose(w, 0.5)
 
 
+def test_route_ties_among_many_experts():
+    """Rows long enough that a sort which is not stable reorders equal logits (short rows hide that)."""
+    rng = np.random.default_rng(5)
+    E, k = 64, 8
+    g = rng.integers(0, 3, size=(200, E)).astype(np.float32)      # three distinct values: ties everywhere
+    ids, _ = orc.route_topk(g, k)
+    for t in range(g.shape[0]):
+        want = sorted(range(E), key=lambda e: (-float(g[t, e]), e))[:k]
+        assert ids[t].tolist() == want
+
+
 def test_route_fig2_example():
     for row in read_golden("routing_fig2.txt"):
         bar = row.index("|")
